@@ -1,0 +1,163 @@
+/*
+ * llamarl.h -- C ABI of the MI355X (gfx950) library for the trainer-side hot
+ * path of LlamaRL's asynchronous off-policy update ("AIPO", paper Sec. 6):
+ *
+ *   1. llamarl_token_logprobs      log pi(y_t | x, y_<t) of the sampled tokens
+ *                                  under the learner, over the full vocabulary
+ *   2. llamarl_offpolicy_loss_fwd  importance ratio pi/mu, one-sided clip at
+ *                                  rho, advantage weighting, masked means
+ *   3. llamarl_offpolicy_loss_bwd  gradients w.r.t. hidden states and LM head
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers (HIP global memory on the current
+ *    device) unless a parameter says "host".  The caller owns every buffer,
+ *    including the workspace; the library allocates nothing, keeps no state
+ *    between calls, never synchronises and enqueues work only on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Matrices are dense row-major: H [N,d], W [V,d], dH [N,d], dW [V,d].
+ *    N = B*T token rows; row t belongs to generation b = t / T.
+ *  - Every call validates its arguments on the host first.  On any error it
+ *    returns a non-zero status, launches nothing and leaves outputs untouched;
+ *    llamarl_last_error() then returns a message (thread-local storage).
+ *  - Pointers must be 16-byte aligned (anything hipMalloc/torch returns is).
+ *  - dtype LLAMARL_BF16 needs d % 8 == 0, LLAMARL_F32 needs d % 4 == 0
+ *    (16-byte rows).  N, V are arbitrary (>= 1).  N*d, V*d element counts may
+ *    exceed 2^32 bytes; single rows may not.
+ *  - Results are deterministic: the same inputs give the same bits, run to run
+ *    (no floating-point atomics anywhere).
+ */
+#ifndef LLAMARL_H
+#define LLAMARL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LLAMARL_OK = 0,
+  LLAMARL_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad enum */
+  LLAMARL_ERR_UNSUPPORTED = 2, /* shape the kernels cannot take (d not a multiple of the 16-byte row unit, ...) */
+  LLAMARL_ERR_WORKSPACE = 3,   /* workspace null or smaller than llamarl_workspace_bytes() says */
+  LLAMARL_ERR_HIP = 4          /* a HIP runtime call (launch, attribute) failed */
+} llamarl_status;
+
+typedef enum { LLAMARL_F32 = 0, LLAMARL_BF16 = 1 } llamarl_dtype;
+
+/* How the importance ratio r = pi/mu is clipped.
+ *  AIPO: w = min(r, rho), used as a constant weight on grad log pi
+ *        (Sec. 6, display equation of the update; "clip ... from above").
+ *  PPO : min(r A, clip(r, 1-eps_lo, 1+eps_hi) A), differentiated through r, so
+ *        the gradient is zero on a clipped branch (App. A, display equation). */
+typedef enum { LLAMARL_CLIP_AIPO = 0, LLAMARL_CLIP_PPO = 1 } llamarl_clip;
+
+/* What the weighted token sum is divided by.  The paper writes the sum over
+ * the tokens of one generation only (Sec. 6); batch aggregation is a choice. */
+typedef enum {
+  LLAMARL_NORM_TOKEN_MEAN = 0,  /* Z = number of valid tokens in the batch (at least 1)            */
+  LLAMARL_NORM_SEQ_MEAN = 1,    /* Z_t = len(b(t)) * number of non-empty generations               */
+  LLAMARL_NORM_SUM_T_MEAN_B = 2 /* Z = B: the paper's plain sum over t, averaged over generations  */
+} llamarl_norm;
+
+typedef struct {
+  float rho;     /* AIPO clip constant; the paper reports rho in [2,10] works well; +inf = unclipped */
+  int clip_mode; /* llamarl_clip */
+  float eps_lo;  /* PPO mode only */
+  float eps_hi;  /* PPO mode only */
+  int norm_mode; /* llamarl_norm */
+} llamarl_loss_params;
+
+typedef enum { LLAMARL_PASS_LOGPROBS = 0, LLAMARL_PASS_LOSS_FWD = 1, LLAMARL_PASS_LOSS_BWD = 2 } llamarl_pass;
+
+/* Bytes of device workspace the given entry point needs for these sizes
+ * (for LLAMARL_PASS_LOSS_FWD pass N = B*T; d, V, dt are ignored).
+ * Returns 0 for invalid sizes.  Host-only computation, no HIP call. */
+size_t llamarl_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, llamarl_pass pass);
+
+/* Message for the last non-OK status returned on this thread ("" if none). */
+const char* llamarl_last_error(void);
+
+/* Library version string (static storage). */
+const char* llamarl_version(void);
+
+/*
+ * Per-token log-probability of the sampled token under the learner policy
+ * (Sec. 6: pi factorises token-wise; the head is z = H W^T, natural-log softmax
+ * over all V entries, no bias, no scaling):
+ *     lse[t]  = log sum_v exp(<H[t,:], W[v,:]>)
+ *     logp[t] = <H[t,:], W[targets[t],:]> - lse[t]
+ * The [N,V] logits exist only as MFMA accumulator tiles; they never reach HBM.
+ *
+ *   H, W      in  [N,d], [V,d] of type dt
+ *   targets   in  int32 [N]
+ *   mask      in  uint8 [N] or NULL (= all valid).  Rows with mask == 0, and
+ *                 rows whose target is outside [0,V), get logp = lse = 0
+ *                 whatever H holds there.
+ *   logp,lse  out float [N]
+ *   ws        scratch, >= llamarl_workspace_bytes(N,d,V,dt,LLAMARL_PASS_LOGPROBS)
+ * Accumulation is fp32 for both dtypes.
+ */
+llamarl_status llamarl_token_logprobs(const void* H, const void* W, const int32_t* targets, const uint8_t* mask,
+                                      int64_t N, int64_t d, int64_t V, llamarl_dtype dt, float* logp, float* lse,
+                                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Importance-weighted clipped policy-gradient loss (Sec. 6 display equation;
+ * App. A for the PPO mode).  With delta = logp - mu_logp, r = exp(delta):
+ *     AIPO  coef[t] = -mask * min(r, rho) * A / Z_t          (= dloss/dlogp[t])
+ *           loss    = sum_t coef[t] * logp[t]   (the weight is a constant:
+ *                     descending this loss follows the paper's ascent update)
+ *     PPO   loss    = -sum_t mask * min(r A, clip(r,1-eps_lo,1+eps_hi) A) / Z_t
+ *           coef[t] = -mask * A * r / Z_t on the unclipped branch, else 0
+ *
+ *   logp, mu_logp  in  float [B*T]; mu_logp is the natural-log probability of
+ *                      y_t under the generator, as shipped with the tokens
+ *   adv            in  float [B] if adv_per_token == 0 (one advantage per
+ *                      generation, broadcast over its tokens), else float [B*T]
+ *   mask           in  uint8 [B*T] response mask (NULL = all valid).  Masking is
+ *                      a select: NaN/Inf at masked positions never leak.
+ *   targets, V     in  optional (targets may be NULL): an unmasked row whose
+ *                      target is outside [0,V) is treated as masked and counted
+ *   p              in  HOST pointer
+ *   loss           out float [1]
+ *   coef           out float [B*T]; exactly 0 at masked rows
+ *   stats          out float [5]: valid tokens, mean r, clipped fraction
+ *                      (r > rho strictly in AIPO mode), mean delta, bad targets
+ *   ws             scratch, >= llamarl_workspace_bytes(B*T,0,0,0,LLAMARL_PASS_LOSS_FWD)
+ */
+llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_logp, const float* adv,
+                                          int adv_per_token, const uint8_t* mask, const int32_t* targets, int64_t V,
+                                          int64_t B, int64_t T, const llamarl_loss_params* p, float* loss,
+                                          float* coef, float* stats, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the loss through logp[t] = z[t,y_t] - lse[t] (chain rule on the
+ * Sec. 6 update, which is a weighted sum of grad log pi(y_t|.)).  Logits are
+ * recomputed tile by tile:
+ *     dz[t,v] = grad_loss * coef[t] * (1[v == targets[t]] - exp(z[t,v] - lse[t]))
+ *     dH = dz W          dW = dz^T H      (fp32 accumulation)
+ * dz is staged in the workspace in type dt; the logits themselves are not.
+ *
+ *   H, W, targets  in  as in llamarl_token_logprobs
+ *   lse            in  float [N] from llamarl_token_logprobs
+ *   coef           in  float [N] from llamarl_offpolicy_loss_fwd; rows with
+ *                      coef == 0 contribute nothing and get a zero dH row
+ *                      whatever H, lse hold there
+ *   grad_loss      in  upstream scalar dL/dloss (host value, usually 1)
+ *   dH             out [N,d] of type dt
+ *   dW             out [V,d] of type dW_dt (LLAMARL_F32 or dt); if
+ *                      accumulate_dW != 0 the result is added to what dW holds
+ *   ws             scratch, >= llamarl_workspace_bytes(N,d,V,dt,LLAMARL_PASS_LOSS_BWD)
+ */
+llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const int32_t* targets, const float* lse,
+                                          const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
+                                          llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
+                                          int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLAMARL_H */

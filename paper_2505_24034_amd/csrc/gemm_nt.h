@@ -1,0 +1,200 @@
+// gemm_nt.h -- the one MFMA main loop every contraction of the path runs on.
+//
+// C[m,n] = sum_k A[m,k] * B[n,k]   ("NT": both operands are K-contiguous), fp32 accumulate.
+//   forward / recompute : A = H [N,d]        B = W   [V,d]     K = d
+//   dH = dz W           : A = dz [N,V]       B = W^T [d,V]     K = V
+//   dW = dz^T H         : A = dz^T [V,N]     B = H^T [d,N]     K = N
+//
+// gfx950 mapping
+//   - one workgroup = 8 wavefronts (2 x 4) = one 256 x 256 output tile; a wavefront owns 128 x 64 of it
+//     as 4 x 2 MFMA 32x32 blocks (128 fp32 accumulator registers per lane).
+//   - K advances in slabs of 128 bytes per row (64 bf16 / 32 fp32).  A slab of both operands is 64 KB of LDS;
+//     two slabs are resident (128 of the CU's 160 KB) so the next slab streams in while this one is multiplied.
+//   - slabs go HBM/L2 -> LDS with buffer loads that write LDS directly (16 bytes per lane, no VGPR staging).
+//     The hardware puts lane i's 16 bytes at LDS base + 16 i, so the bank-conflict swizzle is applied on the
+//     global side: physical 16-byte slot p of row r holds logical chunk p ^ (r & 7).
+//   - out-of-range rows and the K tail use the buffer descriptor's bounds check: such lanes read zeros.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace llamarl {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+constexpr int BM = 256;       // tile rows (A rows)
+constexpr int BN = 256;       // tile cols (B rows)
+constexpr int NTHREADS = 512;
+constexpr int WAVES_N = 4;    // wave grid 2 (M) x 4 (N)
+constexpr int TM = 4;         // 32x32 MFMA blocks per wave along M  (128 rows)
+constexpr int TN = 2;         // ... along N                          (64 cols)
+constexpr int WAVE_M = TM * 32;
+constexpr int WAVE_N = TN * 32;
+constexpr int SLAB_ROW_BYTES = 128;
+constexpr int SLAB_A_BYTES = BM * SLAB_ROW_BYTES;                 // 32 KB
+constexpr int STAGE_BYTES = (BM + BN) * SLAB_ROW_BYTES;           // 64 KB
+constexpr int MAINLOOP_LDS_BYTES = 2 * STAGE_BYTES;               // 128 KB
+constexpr uint32_t OOB_OFFSET = 0x80000000u;                      // beyond any descriptor range used here
+
+struct BF16 {
+  typedef uint16_t store_t;
+  typedef bf16x8_t frag_t;
+  static constexpr int EPC = 8;  // elements per 16-byte chunk
+};
+struct F32 {
+  typedef float store_t;
+  typedef f32x4_t frag_t;
+  static constexpr int EPC = 4;
+};
+
+__device__ __forceinline__ void mma(const bf16x8_t& a, const bf16x8_t& b, f32x16_t& c) {
+  c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// fp32: the 32x32x2 MFMA takes one float per lane (k = lane / 32).  A lane holds 4 consecutive k of one chunk;
+// the two half-waves hold different chunks, so four MFMAs cover the 8 k values of a chunk pair.
+__device__ __forceinline__ void mma(const f32x4_t& a, const f32x4_t& b, f32x16_t& c) {
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Where the accumulator element (i, j, r) of this lane sits inside the 256 x 256 tile.
+// MFMA 32x32 output layout: register r of lane l holds row (r/4)*8 + (l/32)*4 + r%4, column l%32.
+struct LanePos {
+  int wm, wn, lane;
+  __device__ __forceinline__ int row(int i, int r) const {
+    return wm * WAVE_M + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+  }
+  __device__ __forceinline__ int col(int j) const { return wn * WAVE_N + j * 32 + (lane & 31); }
+};
+
+// blockIdx -> (tile_m, tile_n).  Workgroups are dealt round-robin to the 8 XCDs, each with a private L2: give
+// every XCD a contiguous run of tile ids, and order ids so that 32 consecutive ones form an 8 x 4 patch that
+// shares A and B panels.
+__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int nblk = gridDim.x;
+  const int bid = blockIdx.x;
+  const int xcd = bid & 7, local = bid >> 3;
+  const int id = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
+  constexpr int GROUP_M = 8;
+  const int per_group = GROUP_M * tiles_n;
+  const int g = id / per_group;
+  const int first_m = g * GROUP_M;
+  const int gsize = min(tiles_m - first_m, GROUP_M);
+  const int in_g = id - g * per_group;
+  tm = first_m + in_g % gsize;
+  tn = in_g / gsize;
+}
+
+// One operand slab stream: 256 rows x 128 bytes per step, this thread's four 16-byte chunks.
+template <typename TT>
+struct SlabLoader {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t voff[4];       // per-lane byte offset of (row, logical chunk) inside the tile, k = 0
+  uint32_t chunk_k[4];    // first k (elements) of that logical chunk inside a slab
+  int lds_row0[4];        // first row of the 8-row group this wave-instruction fills
+
+  // base: first row of the tile; ld in elements; rows_valid <= 256 rows exist from base on.
+  __device__ __forceinline__ void init(const void* base, int64_t ld, int rows_valid, int wave, int lane) {
+    const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
+    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(row_bytes * (uint32_t)rows_valid),
+                                             0x00020000);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int r0 = (it * 8 + wave) * 8;
+      const int row = r0 + (lane >> 3);
+      const int c = (lane & 7) ^ (row & 7);
+      lds_row0[it] = r0;
+      chunk_k[it] = (uint32_t)(c * TT::EPC);
+      voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + (uint32_t)c * 16u : OOB_OFFSET;
+    }
+  }
+  // k0: first k of the slab (elements); K: contraction length.  lds: start of this operand's slab in LDS.
+  __device__ __forceinline__ void issue(char* lds, int64_t k0, int64_t K) const {
+    const int soff = (int)(k0 * (int64_t)sizeof(typename TT::store_t));
+    const bool tail = k0 + 8 * TT::EPC > K;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      uint32_t v = voff[it];
+      if (tail && k0 + chunk_k[it] >= K) v = OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(lds + lds_row0[it] * SLAB_ROW_BYTES), 16, (int)v,
+                                               soff, 0, 0);
+    }
+  }
+};
+
+// The main loop.  A_tile/B_tile point at the first row of this tile's operand panels.
+// smem must hold MAINLOOP_LDS_BYTES.  Waves leave the loop at different times: a caller that reuses smem
+// must __syncthreads() first.
+template <typename TT>
+__device__ __forceinline__ void gemm_nt_mainloop(const void* A_tile, int64_t lda, int rowsA, const void* B_tile,
+                                                 int64_t ldb, int rowsB, int64_t K, char* smem,
+                                                 f32x16_t (&acc)[TM][TN]) {
+  typedef typename TT::frag_t frag_t;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  constexpr int BK = 8 * TT::EPC;
+
+  SlabLoader<TT> la, lb;
+  la.init(A_tile, lda, rowsA, wave, lane);
+  lb.init(B_tile, ldb, rowsB, wave, lane);
+
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (int)((K + BK - 1) / BK);
+  la.issue(smem, 0, K);
+  lb.issue(smem + SLAB_A_BYTES, 0, K);
+
+  // per-lane read addresses: row = lane % 32 inside a 32-row block, chunk pair (2s, 2s+1) split over half-waves
+  const int sw = lane & 7;
+  const int half = lane >> 5;
+  const int a_row_off = (wm * WAVE_M + (lane & 31)) * SLAB_ROW_BYTES;
+  const int b_row_off = SLAB_A_BYTES + (wn * WAVE_N + (lane & 31)) * SLAB_ROW_BYTES;
+
+  for (int kt = 0; kt < nk; ++kt) {
+    wait_vmcnt0();      // this thread's loads of slab kt have landed in LDS
+    __syncthreads();    // ... everyone's have, and everyone is done reading the other stage
+    if (kt + 1 < nk) {
+      char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+      la.issue(nxt, (int64_t)(kt + 1) * BK, K);
+      lb.issue(nxt + SLAB_A_BYTES, (int64_t)(kt + 1) * BK, K);
+    }
+    const char* cur = smem + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int coff = ((2 * s + half) ^ sw) * 16;
+      frag_t fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[i] = *reinterpret_cast<const frag_t*>(cur + a_row_off + i * 32 * SLAB_ROW_BYTES + coff);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[j] = *reinterpret_cast<const frag_t*>(cur + b_row_off + j * 32 * SLAB_ROW_BYTES + coff);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) mma(fa[i], fb[j], acc[i][j]);
+    }
+  }
+}
+
+}  // namespace llamarl

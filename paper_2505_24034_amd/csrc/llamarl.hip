@@ -1,0 +1,289 @@
+// llamarl.hip -- host side of the C ABI declared in include/llamarl.h: argument validation, workspace
+// layout and kernel launches.  No allocation, no synchronisation, no state between calls.
+#include "../../include/llamarl.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "head_kernels.h"
+#include "loss_kernels.h"
+
+using namespace llamarl;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+llamarl_status fail(llamarl_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t esize(llamarl_dtype dt) { return dt == LLAMARL_BF16 ? 2 : 4; }
+
+// ---- workspace layouts (every block 256-byte aligned) ----------------------------------------------------
+struct FwdWs {
+  int tiles_m, tiles_n;
+  int64_t n_pad;
+  size_t off_m, off_s, off_zt, total;
+};
+FwdWs fwd_ws(int64_t N, int64_t V) {
+  FwdWs w;
+  w.tiles_m = (int)((N + BM - 1) / BM);
+  w.tiles_n = (int)((V + BN - 1) / BN);
+  w.n_pad = round_up(N, BM);
+  const size_t plane = (size_t)w.tiles_n * (size_t)w.n_pad * sizeof(float);
+  w.off_m = 0;
+  w.off_s = round_up((int64_t)plane, 256);
+  w.off_zt = w.off_s + round_up((int64_t)plane, 256);
+  w.total = w.off_zt + (size_t)round_up(w.n_pad * (int64_t)sizeof(float), 256);
+  return w;
+}
+
+struct LossWs {
+  int nblocks;
+  size_t off_len, off_bad, off_part, total;
+};
+LossWs loss_ws(int64_t N) {  // sized for the worst case B = N
+  LossWs w;
+  w.nblocks = (int)((N + LOSS_BLOCK_TOKENS - 1) / LOSS_BLOCK_TOKENS);
+  w.off_len = 0;
+  w.off_bad = (size_t)round_up(N * 4, 256);
+  w.off_part = w.off_bad + (size_t)round_up(N * 4, 256);
+  w.total = w.off_part + (size_t)round_up((int64_t)w.nblocks * LOSS_NSUM * 8, 256);
+  return w;
+}
+
+struct BwdWs {
+  int64_t ldz, ldzt;  // padded leading dimensions (elements): V and N rounded up to 64
+  size_t off_dz, off_dzt, off_wt, off_ht, total;
+};
+BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
+  BwdWs w;
+  const size_t es = esize(dt);
+  w.ldz = round_up(V, 64);
+  w.ldzt = round_up(N, 64);
+  w.off_dz = 0;
+  w.off_dzt = w.off_dz + (size_t)round_up(N * w.ldz * (int64_t)es, 256);
+  w.off_wt = w.off_dzt + (size_t)round_up(V * w.ldzt * (int64_t)es, 256);
+  w.off_ht = w.off_wt + (size_t)round_up(d * w.ldz * (int64_t)es, 256);
+  w.total = w.off_ht + (size_t)round_up(d * w.ldzt * (int64_t)es, 256);
+  return w;
+}
+
+llamarl_status check_head_shape(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
+  if (dt != LLAMARL_F32 && dt != LLAMARL_BF16) return fail(LLAMARL_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  if (N <= 0 || d <= 0 || V <= 0)
+    return fail(LLAMARL_ERR_INVALID_ARG, "N, d, V must be positive (got %lld, %lld, %lld)", (long long)N,
+                (long long)d, (long long)V);
+  const int epc = dt == LLAMARL_BF16 ? 8 : 4;
+  if (d % epc != 0)
+    return fail(LLAMARL_ERR_UNSUPPORTED, "d = %lld must be a multiple of %d for this dtype (16-byte rows)",
+                (long long)d, epc);
+  // one 256-row operand panel must stay below 2^31 bytes (32-bit buffer offsets)
+  const int64_t widest = (d > V ? d : V) > N ? (d > V ? d : V) : N;
+  if (round_up(widest, 64) * (int64_t)esize(dt) * 256 >= (int64_t)1 << 31)
+    return fail(LLAMARL_ERR_UNSUPPORTED, "a 256-row panel of %lld elements per row exceeds 2 GiB", (long long)widest);
+  if ((N + BM - 1) / BM * ((V + BN - 1) / BN) >= (int64_t)1 << 31 || V >= (int64_t)1 << 31)
+    return fail(LLAMARL_ERR_UNSUPPORTED, "too many tiles");
+  return LLAMARL_OK;
+}
+
+template <typename K>
+hipError_t set_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             bytes);
+}
+
+#define HIP_TRY(expr)                                                                              \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return fail(LLAMARL_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename TT>
+llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t Nn,
+                                 int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, hipStream_t st) {
+  StoreArgs a;
+  a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.M = M; a.Nn = Nn; a.K = K;
+  a.tiles_m = (int)((M + BM - 1) / BM);
+  a.tiles_n = (int)((Nn + BN - 1) / BN);
+  a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
+  HIP_TRY(set_lds(k_gemm_store<TT>, MAINLOOP_LDS_BYTES));
+  k_gemm_store<TT><<<dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
+template <typename TT>
+llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets, const uint8_t* mask, int64_t N,
+                            int64_t d, int64_t V, float* logp, float* lse, char* ws, hipStream_t st) {
+  const FwdWs w = fwd_ws(N, V);
+  FwdArgs a;
+  a.H = H; a.W = W; a.targets = targets; a.N = N; a.d = d; a.V = V;
+  a.tiles_m = w.tiles_m; a.tiles_n = w.tiles_n; a.n_pad = w.n_pad;
+  a.part_m = reinterpret_cast<float*>(ws + w.off_m);
+  a.part_s = reinterpret_cast<float*>(ws + w.off_s);
+  a.zt = reinterpret_cast<float*>(ws + w.off_zt);
+  HIP_TRY(set_lds(k_fwd_partials<TT>, MAINLOOP_LDS_BYTES));
+  k_fwd_partials<TT><<<dim3((unsigned)(w.tiles_m * w.tiles_n)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
+  HIP_TRY(hipGetLastError());
+  k_merge_logp<<<dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, targets, mask, N, V,
+                                                                       w.tiles_n, w.n_pad, logp, lse);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
+template <typename TT>
+llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, const float* lse, const float* coef,
+                       float g, int64_t N, int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
+                       llamarl_dtype dW_dt, int accumulate_dW, char* ws, hipStream_t st) {
+  typedef typename TT::store_t stt;
+  const BwdWs w = bwd_ws(N, d, V, dt);
+  stt* dz = reinterpret_cast<stt*>(ws + w.off_dz);
+  stt* dzt = reinterpret_cast<stt*>(ws + w.off_dzt);
+  stt* wt = reinterpret_cast<stt*>(ws + w.off_wt);
+  stt* ht = reinterpret_cast<stt*>(ws + w.off_ht);
+
+  // operand panels for the two gradient contractions: W^T [d][ldz], H^T [d][ldzt] (rows with coef == 0 zeroed)
+  k_transpose<stt><<<dim3((unsigned)(w.ldz / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
+      reinterpret_cast<const stt*>(W), V, d, d, wt, w.ldz, nullptr);
+  HIP_TRY(hipGetLastError());
+  k_transpose<stt><<<dim3((unsigned)(w.ldzt / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
+      reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, coef);
+  HIP_TRY(hipGetLastError());
+
+  // recompute logits tile by tile, turn them into dz in both orientations
+  DzArgs a;
+  a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
+  a.tiles_m = (int)((N + BM - 1) / BM);
+  a.tiles_n = (int)((V + BN - 1) / BN);
+  a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt;
+  const int dz_lds = sizeof(stt) == 2 ? (DZ_LDS_BYTES > MAINLOOP_LDS_BYTES ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES)
+                                      : MAINLOOP_LDS_BYTES;
+  HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
+  k_bwd_dz<TT><<<dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(NTHREADS), dz_lds, st>>>(a);
+  HIP_TRY(hipGetLastError());
+
+  // dH [N,d] = dz [N,V] . W^T[d,V]^T      (K = V, zero-padded to ldz)
+  llamarl_status s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dH, d, dt == LLAMARL_F32, 0, st);
+  if (s != LLAMARL_OK) return s;
+  // dW [V,d] = dz^T [V,N] . H^T[d,N]^T    (K = N, zero-padded to ldzt)
+  return launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* llamarl_last_error(void) { return g_err; }
+const char* llamarl_version(void) { return "llamarl-mi355x 0.1 (gfx950)"; }
+
+size_t llamarl_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, llamarl_pass pass) {
+  if (N <= 0) return 0;
+  switch (pass) {
+    case LLAMARL_PASS_LOGPROBS:
+      if (V <= 0) return 0;
+      return fwd_ws(N, V).total;
+    case LLAMARL_PASS_LOSS_FWD:
+      return loss_ws(N).total;
+    case LLAMARL_PASS_LOSS_BWD:
+      if (V <= 0 || d <= 0 || (dt != LLAMARL_F32 && dt != LLAMARL_BF16)) return 0;
+      return bwd_ws(N, d, V, dt).total;
+    default:
+      return 0;
+  }
+}
+
+llamarl_status llamarl_token_logprobs(const void* H, const void* W, const int32_t* targets, const uint8_t* mask,
+                                      int64_t N, int64_t d, int64_t V, llamarl_dtype dt, float* logp, float* lse,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  if (!H || !W || !targets || !logp || !lse) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  llamarl_status s = check_head_shape(N, d, V, dt);
+  if (s != LLAMARL_OK) return s;
+  if (!aligned16(H) || !aligned16(W)) return fail(LLAMARL_ERR_INVALID_ARG, "H and W must be 16-byte aligned");
+  const size_t need = fwd_ws(N, V).total;
+  if (!ws || ws_bytes < need)
+    return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, need);
+  if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (dt == LLAMARL_BF16)
+    return run_logprobs<BF16>(H, W, targets, mask, N, d, V, logp, lse, reinterpret_cast<char*>(ws), st);
+  return run_logprobs<F32>(H, W, targets, mask, N, d, V, logp, lse, reinterpret_cast<char*>(ws), st);
+}
+
+llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_logp, const float* adv,
+                                          int adv_per_token, const uint8_t* mask, const int32_t* targets, int64_t V,
+                                          int64_t B, int64_t T, const llamarl_loss_params* p, float* loss,
+                                          float* coef, float* stats, void* ws, size_t ws_bytes, void* stream) {
+  if (!logp || !mu_logp || !adv || !p || !loss || !coef || !stats)
+    return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  if (B <= 0 || T <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "B and T must be positive");
+  if (B >= ((int64_t)1 << 31) || T >= ((int64_t)1 << 31) || B * T >= ((int64_t)1 << 40))
+    return fail(LLAMARL_ERR_UNSUPPORTED, "batch too large");
+  if (p->clip_mode != LLAMARL_CLIP_AIPO && p->clip_mode != LLAMARL_CLIP_PPO)
+    return fail(LLAMARL_ERR_INVALID_ARG, "unknown clip_mode %d", p->clip_mode);
+  if (p->norm_mode < 0 || p->norm_mode > 2) return fail(LLAMARL_ERR_INVALID_ARG, "unknown norm_mode %d", p->norm_mode);
+  if (p->clip_mode == LLAMARL_CLIP_AIPO && !(p->rho > 0.f))
+    return fail(LLAMARL_ERR_INVALID_ARG, "rho must be positive (got %g)", (double)p->rho);
+  if (p->clip_mode == LLAMARL_CLIP_PPO && (!(p->eps_lo >= 0.f) || !(p->eps_hi >= 0.f) || p->eps_lo > 1.f))
+    return fail(LLAMARL_ERR_INVALID_ARG, "PPO mode needs 0 <= eps_lo <= 1 and eps_hi >= 0");
+  if (targets && V <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "targets given but V <= 0");
+  const int64_t N = B * T;
+  const LossWs w = loss_ws(N);
+  if (!ws || ws_bytes < w.total)
+    return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, w.total);
+  if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* wsb = reinterpret_cast<char*>(ws);
+  LossArgs a;
+  a.logp = logp; a.mu_logp = mu_logp; a.adv = adv; a.mask = mask; a.targets = targets; a.V = V; a.B = B; a.T = T;
+  a.adv_per_token = adv_per_token; a.rho = p->rho; a.clip_mode = p->clip_mode; a.eps_lo = p->eps_lo;
+  a.eps_hi = p->eps_hi; a.norm_mode = p->norm_mode;
+  a.seq_len = reinterpret_cast<int32_t*>(wsb + w.off_len);
+  a.seq_bad = reinterpret_cast<int32_t*>(wsb + w.off_bad);
+  a.partials = reinterpret_cast<double*>(wsb + w.off_part);
+  a.nblocks = w.nblocks; a.coef = coef; a.loss = loss; a.stats = stats;
+  k_seq_lengths<<<dim3((unsigned)B), dim3(LOSS_THREADS), 0, st>>>(a);
+  HIP_TRY(hipGetLastError());
+  k_loss_tokens<<<dim3((unsigned)w.nblocks), dim3(LOSS_THREADS), 0, st>>>(a);
+  HIP_TRY(hipGetLastError());
+  k_loss_finish<<<dim3(1), dim3(LOSS_THREADS), 0, st>>>(a);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
+llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const int32_t* targets, const float* lse,
+                                          const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
+                                          llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
+                                          int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
+  if (!H || !W || !targets || !lse || !coef || !dH || !dW) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  llamarl_status s = check_head_shape(N, d, V, dt);
+  if (s != LLAMARL_OK) return s;
+  if (dW_dt != LLAMARL_F32 && dW_dt != dt)
+    return fail(LLAMARL_ERR_INVALID_ARG, "dW_dt must be LLAMARL_F32 or equal to dt");
+  if (!aligned16(H) || !aligned16(W) || !aligned16(dH) || !aligned16(dW))
+    return fail(LLAMARL_ERR_INVALID_ARG, "H, W, dH, dW must be 16-byte aligned");
+  if (!std::isfinite(grad_loss)) return fail(LLAMARL_ERR_INVALID_ARG, "grad_loss must be finite");
+  const size_t need = bwd_ws(N, d, V, dt).total;
+  if (!ws || ws_bytes < need)
+    return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, need);
+  if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (dt == LLAMARL_BF16)
+    return run_bwd<BF16>(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW,
+                         reinterpret_cast<char*>(ws), st);
+  return run_bwd<F32>(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW,
+                      reinterpret_cast<char*>(ws), st);
+}
+
+}  // extern "C"

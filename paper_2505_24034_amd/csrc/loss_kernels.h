@@ -1,0 +1,197 @@
+// loss_kernels.h -- the streaming part of the path: importance ratio, clip, advantage weighting and the
+// masked sequence / batch means (paper Sec. 6 display equation; App. A for the PPO mode).
+// HBM-bound: ~21 bytes per token in, 4 out.  Reductions use wavefront shuffles, then one fixed-order
+// cross-block pass in fp64, so results are bitwise reproducible.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace llamarl {
+
+constexpr int LOSS_THREADS = 256;
+constexpr int LOSS_ITEMS = 4;                                 // tokens per thread
+constexpr int LOSS_BLOCK_TOKENS = LOSS_THREADS * LOSS_ITEMS;  // 1024
+constexpr int LOSS_NSUM = 5;                                  // loss, sum r, clipped count, sum delta, valid count
+
+struct LossArgs {
+  const float* logp;
+  const float* mu_logp;
+  const float* adv;
+  const uint8_t* mask;
+  const int32_t* targets;
+  int64_t V;
+  int64_t B, T;
+  int adv_per_token;
+  float rho;
+  int clip_mode;
+  float eps_lo, eps_hi;
+  int norm_mode;
+  int32_t* seq_len;    // [B] valid tokens per generation
+  int32_t* seq_bad;    // [B] unmasked tokens with an out-of-range target
+  double* partials;    // [nblocks][LOSS_NSUM]
+  int nblocks;
+  float* coef;
+  float* loss;
+  float* stats;
+};
+
+__device__ __forceinline__ bool token_valid(const LossArgs& a, int64_t t, bool* bad) {
+  const bool m = (a.mask == nullptr) || (a.mask[t] != 0);
+  bool b = false;
+  if (m && a.targets != nullptr) {
+    const int y = a.targets[t];
+    b = (y < 0) || ((int64_t)y >= a.V);
+  }
+  *bad = b;
+  return m && !b;
+}
+
+template <typename V>
+__device__ __forceinline__ V wave_sum(V v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// one block per generation: valid-token count and bad-target count
+__global__ __launch_bounds__(LOSS_THREADS) void k_seq_lengths(LossArgs a) {
+  const int b = blockIdx.x;
+  int cnt = 0, nbad = 0;
+  for (int64_t t = threadIdx.x; t < a.T; t += LOSS_THREADS) {
+    bool bad;
+    cnt += token_valid(a, (int64_t)b * a.T + t, &bad) ? 1 : 0;
+    nbad += bad ? 1 : 0;
+  }
+  cnt = wave_sum(cnt);
+  nbad = wave_sum(nbad);
+  __shared__ int s_c[LOSS_THREADS / 64], s_b[LOSS_THREADS / 64];
+  if ((threadIdx.x & 63) == 0) {
+    s_c[threadIdx.x >> 6] = cnt;
+    s_b[threadIdx.x >> 6] = nbad;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int c = 0, d = 0;
+    for (int w = 0; w < LOSS_THREADS / 64; ++w) {
+      c += s_c[w];
+      d += s_b[w];
+    }
+    a.seq_len[b] = c;
+    a.seq_bad[b] = d;
+  }
+}
+
+// coef[t] and per-block partial sums
+__global__ __launch_bounds__(LOSS_THREADS) void k_loss_tokens(LossArgs a) {
+  __shared__ long long s_red[2][LOSS_THREADS / 64];
+  __shared__ double s_sum[LOSS_NSUM][LOSS_THREADS / 64];
+  // every block re-derives the batch normaliser from the B per-generation counts (B is small)
+  long long nv = 0, bv = 0;
+  for (int64_t b = threadIdx.x; b < a.B; b += LOSS_THREADS) {
+    const int l = a.seq_len[b];
+    nv += l;
+    bv += (l > 0) ? 1 : 0;
+  }
+  nv = wave_sum(nv);
+  bv = wave_sum(bv);
+  if ((threadIdx.x & 63) == 0) {
+    s_red[0][threadIdx.x >> 6] = nv;
+    s_red[1][threadIdx.x >> 6] = bv;
+  }
+  __syncthreads();
+  nv = 0;
+  bv = 0;
+  for (int w = 0; w < LOSS_THREADS / 64; ++w) {
+    nv += s_red[0][w];
+    bv += s_red[1][w];
+  }
+  const float n_valid = (float)(nv > 0 ? nv : 1);
+  const float b_valid = (float)(bv > 0 ? bv : 1);
+
+  double acc[LOSS_NSUM] = {0, 0, 0, 0, 0};
+  const int64_t N = a.B * a.T;
+  const int64_t base = (int64_t)blockIdx.x * LOSS_BLOCK_TOKENS;
+#pragma unroll
+  for (int it = 0; it < LOSS_ITEMS; ++it) {
+    const int64_t t = base + it * LOSS_THREADS + threadIdx.x;
+    if (t >= N) continue;
+    bool bad;
+    const bool valid = token_valid(a, t, &bad);
+    float c = 0.f;
+    if (valid) {
+      const int64_t b = t / a.T;
+      const float lp = a.logp[t];
+      const float delta = lp - a.mu_logp[t];
+      const float r = expf(delta);
+      const float A = a.adv_per_token ? a.adv[t] : a.adv[b];
+      float Z;
+      if (a.norm_mode == 0) Z = n_valid;
+      else if (a.norm_mode == 1) Z = b_valid * (float)max(a.seq_len[b], 1);
+      else Z = (float)a.B;
+      bool clipped;
+      float term;
+      if (a.clip_mode == 0) {
+        const float w = fminf(r, a.rho);          // one-sided clip from above; w is a constant weight
+        c = -(w * A) / Z;
+        clipped = r > a.rho;
+        term = c * lp;
+      } else {
+        const float rc = fminf(fmaxf(r, 1.f - a.eps_lo), 1.f + a.eps_hi);
+        const float u = r * A, k = rc * A;
+        const bool active = u <= k;               // the unclipped term is the min: gradient flows through r
+        c = active ? -(A * r) / Z : 0.f;
+        clipped = !active;
+        term = -fminf(u, k) / Z;
+      }
+      acc[0] += (double)term;
+      acc[1] += (double)r;
+      acc[2] += clipped ? 1.0 : 0.0;
+      acc[3] += (double)delta;
+      acc[4] += 1.0;
+    }
+    a.coef[t] = c;
+  }
+#pragma unroll
+  for (int q = 0; q < LOSS_NSUM; ++q) {
+    const double v = wave_sum(acc[q]);
+    if ((threadIdx.x & 63) == 0) s_sum[q][threadIdx.x >> 6] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < LOSS_NSUM) {
+    double v = 0;
+    for (int w = 0; w < LOSS_THREADS / 64; ++w) v += s_sum[threadIdx.x][w];
+    a.partials[(int64_t)blockIdx.x * LOSS_NSUM + threadIdx.x] = v;
+  }
+}
+
+// one block: fixed-order sum of the block partials -> loss, stats
+__global__ __launch_bounds__(LOSS_THREADS) void k_loss_finish(LossArgs a) {
+  __shared__ double s_sum[LOSS_NSUM + 1][LOSS_THREADS / 64];
+  double acc[LOSS_NSUM + 1] = {0, 0, 0, 0, 0, 0};
+  for (int i = threadIdx.x; i < a.nblocks; i += LOSS_THREADS)
+#pragma unroll
+    for (int q = 0; q < LOSS_NSUM; ++q) acc[q] += a.partials[(int64_t)i * LOSS_NSUM + q];
+  for (int64_t b = threadIdx.x; b < a.B; b += LOSS_THREADS) acc[LOSS_NSUM] += (double)a.seq_bad[b];
+#pragma unroll
+  for (int q = 0; q <= LOSS_NSUM; ++q) {
+    const double v = wave_sum(acc[q]);
+    if ((threadIdx.x & 63) == 0) s_sum[q][threadIdx.x >> 6] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t[LOSS_NSUM + 1];
+    for (int q = 0; q <= LOSS_NSUM; ++q) {
+      t[q] = 0;
+      for (int w = 0; w < LOSS_THREADS / 64; ++w) t[q] += s_sum[q][w];
+    }
+    const double den = t[4] > 0 ? t[4] : 1.0;
+    a.loss[0] = (float)t[0];
+    a.stats[0] = (float)t[4];
+    a.stats[1] = (float)(t[1] / den);
+    a.stats[2] = (float)(t[2] / den);
+    a.stats[3] = (float)(t[3] / den);
+    a.stats[4] = (float)t[5];
+  }
+}
+
+}  // namespace llamarl

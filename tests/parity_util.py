@@ -1,0 +1,72 @@
+"""Shared helpers of the GPU parity tests: run the HIP path, run the oracle on
+the same inputs, compare with the tolerances of the benchmark definition."""
+import numpy as np
+import torch
+
+from oracle import aipo_oracle as orc
+from paper_2505_24034_amd import synth
+
+
+def run_hip(lib, x, rho=2.0, norm_mode=0, grad_loss=1.0, clip_mode=0, eps=(0.2, 0.2), dW_dtype=None,
+            pass_targets_to_loss=True):
+    B, T = x["mask"].shape
+    V = x["W"].shape[0]
+    logp, lse = lib.token_logprobs(x["H"], x["W"], x["targets"], x["mask"].reshape(-1))
+    loss, coef, stats = lib.offpolicy_loss_fwd(logp, x["mu_logp"], x["adv"], x["mask"], B, T, rho=rho,
+                                               norm_mode=norm_mode, clip_mode=clip_mode, eps_lo=eps[0],
+                                               eps_hi=eps[1], targets=x["targets"] if pass_targets_to_loss else None,
+                                               V=V)
+    dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef, grad_loss=grad_loss, dW_dtype=dW_dtype)
+    torch.cuda.synchronize()
+    return dict(logp=logp, lse=lse, loss=loss, coef=coef, stats=stats, dH=dH, dW=dW)
+
+
+def run_oracle(x, rho=2.0, norm_mode=0, grad_loss=1.0, clip_mode=0, eps=(0.2, 0.2)):
+    return orc.aipo_step(synth.to_oracle(x["H"]), synth.to_oracle(x["W"]), synth.to_oracle(x["targets"]),
+                         synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]), synth.to_oracle(x["mask"]),
+                         rho, norm_mode, grad_loss, clip_mode, eps[0], eps[1])
+
+
+def f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def check_grad(name, got, ref, dtype):
+    """fp32 workload: |delta| <= 1e-4 everywhere.  bf16 workloads: relative Frobenius error <= 1e-2 and
+    max |delta| <= 1e-2 * max |ref|."""
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, name
+    assert np.all(np.isfinite(got)), name + " has non-finite entries"
+    err = np.abs(got - ref).max() if got.size else 0.0
+    if dtype == "f32":
+        assert err <= 1e-4, "%s: max |delta| = %.3g" % (name, err)
+        return
+    scale = np.abs(ref).max()
+    fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300)
+    assert fro <= 1e-2, "%s: relative Frobenius error %.3g" % (name, fro)
+    assert err <= 1e-2 * scale + 1e-30, "%s: max |delta| = %.3g vs max |ref| = %.3g" % (name, err, scale)
+
+
+def check_all(got, ref, dtype, check_stats=True):
+    tol_lp = 1e-4 if dtype == "f32" else 2e-2
+    lp, lse = f64(got["logp"]), f64(got["lse"])
+    assert np.abs(lp - ref["logp"]).max() <= tol_lp, "logp max |delta| = %.3g" % np.abs(lp - ref["logp"]).max()
+    assert np.abs(lse - ref["lse"]).max() <= tol_lp, "lse max |delta| = %.3g" % np.abs(lse - ref["lse"]).max()
+    coef = f64(got["coef"])
+    # masked rows are exactly zero on both sides
+    assert np.array_equal(coef == 0, ref["coef"] == 0)
+    loss = float(got["loss"].item())
+    if dtype == "f32":
+        assert np.abs(coef - ref["coef"]).max() <= 1e-4
+        assert abs(loss - ref["loss"]) <= 1e-4
+    else:
+        cs = np.abs(ref["coef"]).max()
+        assert np.abs(coef - ref["coef"]).max() <= 2.5e-2 * cs + 1e-30      # coef ~ exp(logp): 2e-2 in logp
+        scale = np.abs(ref["coef"] * ref["logp"]).sum()
+        assert abs(loss - ref["loss"]) <= 1e-2 * scale + 1e-30, (loss, ref["loss"], scale)
+    if check_stats:
+        st = f64(got["stats"])
+        assert st[0] == ref["stats"][0] and st[4] == ref["stats"][4]
+        assert np.allclose(st[1:4], ref["stats"][1:4], rtol=0, atol=(1e-4 if dtype == "f32" else 2.5e-2))
+    check_grad("dH", f64(got["dH"]), ref["dH"], dtype)
+    check_grad("dW", f64(got["dW"]), ref["dW"], dtype)

@@ -1,0 +1,157 @@
+"""GPU parity, exhaustive: every output element of the HIP path against the
+fp64 oracle on the same seeded inputs.  Sizes span several 256x256 tiles with
+ragged tails in N, V and d (the K tail of the 128-byte slabs)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_24034_amd import synth
+from parity_util import check_all, check_grad, f64, run_hip, run_oracle
+
+pytestmark = pytest.mark.gpu
+W8 = synth.WORKLOADS["llama3_8b"]
+W1 = synth.WORKLOADS["tiny_fp32"]
+
+
+def test_config1_tiny_fp32(lib):
+    w = W1
+    x = synth.make_inputs(w, "cuda")
+    got, ref = run_hip(lib, x), run_oracle(x)
+    check_all(got, ref, "f32")
+
+
+@pytest.mark.parametrize("name,w", [
+    ("bf16_ragged", synth.scaled(W8, d=520, V=5000, B=3, T=347, len_lo=40, len_hi=347)),
+    ("bf16_one_tile", synth.scaled(W8, d=64, V=256, B=1, T=256, len_lo=100, len_hi=256)),
+    ("bf16_tiny", synth.scaled(W8, d=8, V=3, B=2, T=5, len_lo=1, len_hi=5)),
+    ("bf16_many_tiles", synth.scaled(W8, d=1024, V=2304, B=5, T=512, len_lo=64, len_hi=512)),
+    ("f32_ragged", synth.scaled(W1, d=100, V=777, B=3, T=100, len_lo=10, len_hi=100)),
+    ("f32_many_tiles", synth.scaled(W1, d=288, V=1300, B=2, T=300, len_lo=30, len_hi=300)),
+])
+def test_exhaustive_parity(lib, name, w):
+    x = synth.make_inputs(w, "cuda")
+    got, ref = run_hip(lib, x, rho=2.0), run_oracle(x, rho=2.0)
+    check_all(got, ref, w.dtype)
+
+
+@pytest.mark.parametrize("rho", [1.0, 1.07])
+@pytest.mark.parametrize("norm_mode", [0, 1, 2])
+def test_clip_engaged_and_norm_modes(lib, rho, norm_mode):
+    # at the paper's rho in [2,10] the clip almost never fires on these inputs: rho near 1 clips ~half / ~16 %
+    w = synth.scaled(W8, d=256, V=1500, B=4, T=200, len_lo=20, len_hi=200, sigma_mu=2e-3 * 4)
+    x = synth.make_inputs(w, "cuda")
+    got, ref = run_hip(lib, x, rho=rho, norm_mode=norm_mode, grad_loss=-1.5), \
+        run_oracle(x, rho=rho, norm_mode=norm_mode, grad_loss=-1.5)
+    assert 0.02 < ref["stats"][2] < 0.98
+    check_all(got, ref, "bf16")
+
+
+def test_fp32_clip_engaged(lib):
+    w = synth.scaled(W1, sigma_mu=3e-2)
+    x = synth.make_inputs(w, "cuda")
+    got, ref = run_hip(lib, x, rho=1.0, norm_mode=1), run_oracle(x, rho=1.0, norm_mode=1)
+    assert 0.1 < ref["stats"][2] < 0.9
+    check_all(got, ref, "f32")
+
+
+def test_results_are_bitwise_reproducible(lib):
+    w = synth.scaled(W8, d=512, V=3000, B=2, T=400, len_lo=50, len_hi=400)
+    x = synth.make_inputs(w, "cuda")
+    a, b = run_hip(lib, x), run_hip(lib, x)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_dW_fp32_output_and_accumulation(lib):
+    w = synth.scaled(W8, d=256, V=700, B=2, T=300, len_lo=50, len_hi=300)
+    x = synth.make_inputs(w, "cuda")
+    ref = run_oracle(x)
+    got = run_hip(lib, x, dW_dtype=torch.float32)
+    assert got["dW"].dtype == torch.float32
+    check_grad("dW(f32)", f64(got["dW"]), ref["dW"], "bf16")
+    dW = got["dW"].clone()
+    lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], got["lse"], got["coef"], dW=dW, accumulate_dW=True)
+    torch.cuda.synchronize()
+    assert torch.allclose(dW, 2 * got["dW"], rtol=1e-6, atol=0)
+    dWb = run_hip(lib, x)["dW"]
+    first = dWb.clone()
+    lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], got["lse"], got["coef"], dW=dWb, accumulate_dW=True)
+    torch.cuda.synchronize()
+    check_grad("dW(bf16, accumulated twice)", f64(dWb), 2 * ref["dW"], "bf16")
+    assert first.dtype == torch.bfloat16
+
+
+def test_masked_rows_with_nan_do_not_leak(lib):
+    w = synth.scaled(W8, d=128, V=600, B=3, T=200, len_lo=20, len_hi=150)
+    x = synth.make_inputs(w, "cuda")
+    ref = run_oracle(x)
+    dead = (x["mask"].reshape(-1) == 0)
+    assert bool(dead.any())
+    x2 = dict(x)
+    x2["H"] = x["H"].clone()
+    x2["H"][dead] = float("nan")
+    x2["mu_logp"] = x["mu_logp"].clone()
+    x2["mu_logp"][dead] = float("inf")
+    got = run_hip(lib, x2)
+    check_all(got, ref, "bf16")
+    assert not bool(got["dH"][dead].any()) and not bool(got["logp"][dead].any()) and not bool(got["coef"][dead].any())
+
+
+def test_all_masked_batch_gives_zeros(lib):
+    w = synth.scaled(W8, d=64, V=300, B=2, T=70, len_lo=5, len_hi=70)
+    x = synth.make_inputs(w, "cuda")
+    x["mask"].zero_()
+    for mode in (0, 1, 2):
+        got = run_hip(lib, x, norm_mode=mode)
+        assert float(got["loss"]) == 0.0 and not bool(got["coef"].any())
+        assert not bool(got["dH"].any()) and not bool(got["dW"].any())
+        assert bool(torch.isfinite(got["stats"]).all()) and float(got["stats"][0]) == 0.0
+
+
+def test_out_of_range_targets_behave_as_masked_and_are_counted(lib):
+    w = synth.scaled(W8, d=64, V=300, B=2, T=70, len_lo=40, len_hi=70)
+    x = synth.make_inputs(w, "cuda")
+    x["targets"][3] = 300
+    x["targets"][5] = -7
+    x["targets"][100] = 2 ** 30
+    got, ref = run_hip(lib, x), run_oracle(x)
+    assert ref["stats"][4] >= 2
+    check_all(got, ref, "bf16")
+
+
+def test_ppo_mode_and_per_token_advantage(lib):
+    w = synth.scaled(W8, d=128, V=900, B=3, T=150, len_lo=30, len_hi=150, sigma_mu=1e-2)
+    x = synth.make_inputs(w, "cuda")
+    got = run_hip(lib, x, clip_mode=1, eps=(0.1, 0.15))
+    ref = run_oracle(x, clip_mode=1, eps=(0.1, 0.15))
+    assert 0.02 < ref["stats"][2] < 0.98
+    # a token whose ratio sits within float rounding of a PPO bound may take either branch: none here
+    r = np.exp(ref["logp"] - f64(x["mu_logp"]))
+    assert np.abs(r - 0.9).min() > 1e-4 and np.abs(r - 1.15).min() > 1e-4
+    check_all(got, ref, "bf16")
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x["adv"] = torch.randn(3, 150, generator=g, device="cuda")
+    got, ref = run_hip(lib, x), run_oracle(x)
+    check_all(got, ref, "bf16")
+
+
+def test_loss_kernel_alone_fp32_exactness_and_infinite_rho(lib):
+    import math
+    from oracle import aipo_oracle as orc
+    g = torch.Generator(device="cuda").manual_seed(11)
+    B, T = 7, 1300
+    logp = -torch.rand(B * T, generator=g, device="cuda") * 12
+    mu = logp + torch.randn(B * T, generator=g, device="cuda") * 0.8
+    mu[17] = -float("inf")
+    adv = torch.randn(B, generator=g, device="cuda")
+    mask = (torch.rand(B, T, generator=g, device="cuda") < 0.6).to(torch.uint8)     # not a prefix mask
+    mask[4] = 0
+    for rho, mode in ((2.0, 0), (math.inf, 1), (3.0, 2)):
+        loss, coef, stats = lib.offpolicy_loss_fwd(logp, mu, adv, mask, B, T, rho=rho, norm_mode=mode)
+        ref = orc.offpolicy_loss_fwd(f64(logp), f64(mu), f64(adv), mask.cpu().numpy(), rho, mode)
+        assert np.allclose(f64(coef), ref["coef"], rtol=3e-6, atol=1e-12)
+        assert float(loss) == pytest.approx(ref["loss"], rel=1e-5, abs=1e-6)
+        st = f64(stats)
+        assert st[0] == ref["stats"][0]
+        if math.isfinite(ref["stats"][1]):
+            assert np.allclose(st[1:4], ref["stats"][1:4], rtol=1e-5, atol=1e-6)
