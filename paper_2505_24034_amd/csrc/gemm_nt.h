@@ -12,7 +12,11 @@
 //     two slabs are resident (128 of the CU's 160 KB) so the next slab streams in while this one is multiplied.
 //   - slabs go HBM/L2 -> LDS with buffer loads that write LDS directly (16 bytes per lane, no VGPR staging).
 //     The hardware puts lane i's 16 bytes at LDS base + 16 i, so the bank-conflict swizzle is applied on the
-//     global side: physical 16-byte slot p of row r holds logical chunk p ^ (r & 7).
+//     global side: physical 16-byte slot p of row r holds logical chunk p ^ ((r >> 1) & 7), which spreads the
+//     16 rows a ds_read_b128 serves per pass over all 64 LDS banks.
+//   - the loop is software-pipelined by hand: MFMA fragments are double-buffered in registers, every
+//     ds_read_b128 is issued in the shadow of an MFMA one k-substep ahead of its use, and scheduling fences
+//     pin that interleave (the compiler's own schedule exposes the LDS latency).
 //   - out-of-range rows and the K tail use the buffer descriptor's bounds check: such lanes read zeros.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -100,6 +104,8 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, i
   tn = in_g / gsize;
 }
 
+__device__ __forceinline__ int swizzle(int row) { return (row >> 1) & 7; }
+
 // One operand slab stream: 256 rows x 128 bytes per step, this thread's four 16-byte chunks.
 template <typename TT>
 struct SlabLoader {
@@ -117,7 +123,7 @@ struct SlabLoader {
     for (int it = 0; it < 4; ++it) {
       const int r0 = (it * 8 + wave) * 8;
       const int row = r0 + (lane >> 3);
-      const int c = (lane & 7) ^ (row & 7);
+      const int c = (lane & 7) ^ swizzle(row);
       lds_row0[it] = r0;
       chunk_k[it] = (uint32_t)(c * TT::EPC);
       voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + (uint32_t)c * 16u : OOB_OFFSET;
@@ -137,9 +143,50 @@ struct SlabLoader {
   }
 };
 
+#define LLAMARL_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <typename TT>
+struct Frags {
+  typename TT::frag_t a[TM];
+  typename TT::frag_t b[TN];
+};
+
+// One k-substep: TM x TN MFMA blocks on `cur`; in the shadow of MFMA q the q-th fragment of the next substep is
+// read into `nxt` (A0 B0 A1 B1 ... then the rest of the longer operand).  rd == nullptr: nothing left to read.
+template <typename TT>
+__device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, const char* rd, int a_addr, int b_addr,
+                                          f32x16_t (&acc)[TM][TN], bool read) {
+  typedef typename TT::frag_t frag_t;
+  constexpr int NR = TM + TN;
+  constexpr int MINAB = TM < TN ? TM : TN;
+#pragma unroll
+  for (int q = 0; q < TM * TN; ++q) {
+    const int i = q / TN, j = q % TN;
+    mma(cur.a[i], cur.b[j], acc[i][j]);
+    LLAMARL_FENCE();
+    if (q < NR && read) {
+      if (q < 2 * MINAB) {
+        if ((q & 1) == 0) nxt.a[q >> 1] = *reinterpret_cast<const frag_t*>(rd + a_addr + (q >> 1) * 32 * SLAB_ROW_BYTES);
+        else nxt.b[q >> 1] = *reinterpret_cast<const frag_t*>(rd + b_addr + (q >> 1) * 32 * SLAB_ROW_BYTES);
+      } else {
+        const int r = q - MINAB;
+        if (TM > TN) nxt.a[r] = *reinterpret_cast<const frag_t*>(rd + a_addr + r * 32 * SLAB_ROW_BYTES);
+        else nxt.b[r] = *reinterpret_cast<const frag_t*>(rd + b_addr + r * 32 * SLAB_ROW_BYTES);
+      }
+      LLAMARL_FENCE();
+    }
+  }
+}
+
 // The main loop.  A_tile/B_tile point at the first row of this tile's operand panels.
 // smem must hold MAINLOOP_LDS_BYTES.  Waves leave the loop at different times: a caller that reuses smem
 // must __syncthreads() first.
+//
+// Per slab kt (4 k-substeps s = 0..3, fragment sets f0/f1 alternate):
+//   s=0..2 : MFMAs of substep s, reads of substep s+1 from slab kt
+//   sync   : wait for this thread's share of slab kt+1, barrier (slab kt+1 visible, slab kt no longer read)
+//   issue  : slab kt+2 -> the buffer slab kt just vacated
+//   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1
 template <typename TT>
 __device__ __forceinline__ void gemm_nt_mainloop(const void* A_tile, int64_t lda, int rowsA, const void* B_tile,
                                                  int64_t ldb, int rowsB, int64_t K, char* smem,
@@ -161,39 +208,57 @@ __device__ __forceinline__ void gemm_nt_mainloop(const void* A_tile, int64_t lda
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (int)((K + BK - 1) / BK);
-  la.issue(smem, 0, K);
-  lb.issue(smem + SLAB_A_BYTES, 0, K);
-
   // per-lane read addresses: row = lane % 32 inside a 32-row block, chunk pair (2s, 2s+1) split over half-waves
-  const int sw = lane & 7;
   const int half = lane >> 5;
-  const int a_row_off = (wm * WAVE_M + (lane & 31)) * SLAB_ROW_BYTES;
-  const int b_row_off = SLAB_A_BYTES + (wn * WAVE_N + (lane & 31)) * SLAB_ROW_BYTES;
+  const int arow = wm * WAVE_M + (lane & 31), brow = wn * WAVE_N + (lane & 31);
+  int a_addr[4], b_addr[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    a_addr[s] = arow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(arow)) * 16);
+    b_addr[s] = SLAB_A_BYTES + brow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(brow)) * 16);
+  }
 
-  for (int kt = 0; kt < nk; ++kt) {
-    wait_vmcnt0();      // this thread's loads of slab kt have landed in LDS
-    __syncthreads();    // ... everyone's have, and everyone is done reading the other stage
-    if (kt + 1 < nk) {
-      char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-      la.issue(nxt, (int64_t)(kt + 1) * BK, K);
-      lb.issue(nxt + SLAB_A_BYTES, (int64_t)(kt + 1) * BK, K);
+  char* buf0 = smem;
+  char* buf1 = smem + STAGE_BYTES;
+  la.issue(buf0, 0, K);
+  lb.issue(buf0 + SLAB_A_BYTES, 0, K);
+  if (nk > 1) {
+    la.issue(buf1, BK, K);
+    lb.issue(buf1 + SLAB_A_BYTES, BK, K);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | 8);   // vmcnt(8): slab 0 landed, the 8 loads of slab 1 may be in flight
+  } else {
+    wait_vmcnt0();
+  }
+  __syncthreads();
+  Frags<TT> f0, f1;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) f0.a[i] = *reinterpret_cast<const frag_t*>(buf0 + a_addr[0] + i * 32 * SLAB_ROW_BYTES);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) f0.b[j] = *reinterpret_cast<const frag_t*>(buf0 + b_addr[0] + j * 32 * SLAB_ROW_BYTES);
+
+  for (int kt = 0; kt < nk - 1; ++kt) {
+    char* cur = smem + (kt & 1) * STAGE_BYTES;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+    LLAMARL_FENCE();
+    k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
+    k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
+    k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
+    wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
+    __syncthreads();    // everyone's has, and everyone is done reading slab kt
+    if (kt + 2 < nk) {
+      la.issue(cur, (int64_t)(kt + 2) * BK, K);
+      lb.issue(cur + SLAB_A_BYTES, (int64_t)(kt + 2) * BK, K);
     }
-    const char* cur = smem + (kt & 1) * STAGE_BYTES;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int coff = ((2 * s + half) ^ sw) * 16;
-      frag_t fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const frag_t*>(cur + a_row_off + i * 32 * SLAB_ROW_BYTES + coff);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const frag_t*>(cur + b_row_off + j * 32 * SLAB_ROW_BYTES + coff);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) mma(fa[i], fb[j], acc[i][j]);
-    }
+    LLAMARL_FENCE();
+    k_substep<TT>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true);
+  }
+  {
+    const char* cur = smem + ((nk - 1) & 1) * STAGE_BYTES;
+    LLAMARL_FENCE();
+    k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
+    k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
+    k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
+    k_substep<TT>(f1, f0, cur, 0, 0, acc, false);
   }
 }
 

@@ -1,36 +1,30 @@
 // head_kernels.h -- the four contractions of the path and their fused epilogues.
 //
-//   k_fwd_partials   logits tile -> per-(row, vocab tile) online-softmax partial (max, sum of exp) and the
+//   k_fwd_partials   logits tile -> per-(vocab tile, token) online-softmax partial (max, sum of exp) and the
 //                    target logit: the [N,V] logits never leave the accumulators (paper Sec. 6: log pi(y_t|.))
 //   k_merge_logp     partials -> lse[t], logp[t]
 //   k_bwd_dz         recomputed logits tile -> dz = g * coef * (onehot - softmax), written in both orientations
 //   k_gemm_store     plain C = A B^T with a store epilogue (dH and dW)
 //   k_transpose      [R,C] -> [C,R] with zero padding (W^T and H^T panels for the two backward contractions)
+//
+// In the two logits kernels the MFMA "row" operand is W (vocab) and the "column" operand is H (tokens): an
+// accumulator lane then holds ONE token (column = lane % 32) and 16 vocab entries per 32x32 block, so the
+// softmax reductions over the vocabulary run inside the lane's own registers, with a single cross-lane step.
 #pragma once
 #include "gemm_nt.h"
 
 namespace llamarl {
 
-constexpr int EPI_LDS_HEADER = 4096;                 // per-row scalars live in the first 4 KB
 constexpr int STAGE_LD = 264;                        // bf16 staging tile row stride (elements): 528 B = 33 chunks
-constexpr int EPI_STAGE_BYTES = BM * STAGE_LD * 2;   // 135168
-constexpr int DZ_LDS_BYTES = EPI_LDS_HEADER + EPI_STAGE_BYTES;   // 139264 <= 160 KB
+constexpr int EPI_STAGE_BYTES = BM * STAGE_LD * 2;   // 135168 <= 160 KB
+constexpr int DZ_LDS_BYTES = EPI_STAGE_BYTES > MAINLOOP_LDS_BYTES ? EPI_STAGE_BYTES : MAINLOOP_LDS_BYTES;
+constexpr float LOG2E = 1.4426950408889634f;
 
-__device__ __forceinline__ float half_wave_max(float v) {   // over the 32 lanes that share lane/32
-  v = fmaxf(v, __shfl_xor(v, 1));
-  v = fmaxf(v, __shfl_xor(v, 2));
-  v = fmaxf(v, __shfl_xor(v, 4));
-  v = fmaxf(v, __shfl_xor(v, 8));
-  v = fmaxf(v, __shfl_xor(v, 16));
-  return v;
-}
-__device__ __forceinline__ float half_wave_sum(float v) {
-  v += __shfl_xor(v, 1);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 8);
-  v += __shfl_xor(v, 16);
-  return v;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // v_cvt_pk_bf16_f32: round to nearest even
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 struct FwdArgs {
@@ -38,103 +32,116 @@ struct FwdArgs {
   const void* W;
   const int32_t* targets;
   int64_t N, d, V;
-  int tiles_m, tiles_n;
-  int64_t n_pad;        // row stride of the partial arrays
-  float* part_m;        // [tiles_n][n_pad] running max of the tile's logits
-  float* part_s;        // [tiles_n][n_pad] sum of exp(logit - max)
-  float* zt;            // [n_pad] target logit, written by the one tile that holds column y_t
+  int tiles_v, tiles_t;   // tiles over the vocabulary (MFMA rows) and over the tokens (MFMA columns)
+  int64_t n_pad;          // row stride of the partial arrays
+  float* part_m;          // [tiles_v][n_pad] max of the tile's logits of a token
+  float* part_s;          // [tiles_v][n_pad] sum of exp(logit - max)
+  float* zt;              // [n_pad] target logit, written by the one tile that holds vocab row y_t
 };
 
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int tm, tn;
-  tile_coords(a.tiles_m, a.tiles_n, tm, tn);
-  const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-  const int rowsA = (int)min((int64_t)BM, a.N - row0);
-  const int rowsB = (int)min((int64_t)BN, a.V - col0);
+  int tv, tt;
+  tile_coords(a.tiles_v, a.tiles_t, tv, tt);
+  const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
+  const int rowsV = (int)min((int64_t)BM, a.V - v0);
+  const int rowsT = (int)min((int64_t)BN, a.N - t0);
   typedef typename TT::store_t st;
   f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.H + row0 * a.d, a.d, rowsA, (const st*)a.W + col0 * a.d, a.d, rowsB, a.d, smem,
-                       acc);
+  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, (const st*)a.H + t0 * a.d, a.d, rowsT, a.d, smem, acc);
 
   const int tid = threadIdx.x;
   LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
   __syncthreads();
-  int* s_tgt = reinterpret_cast<int*>(smem);                 // [256]
-  float* s_m = reinterpret_cast<float*>(smem + 1024);        // [WAVES_N][256]
-  float* s_s = s_m + WAVES_N * BM;                           // [WAVES_N][256]
-  if (tid < BM) s_tgt[tid] = (tid < rowsA) ? a.targets[row0 + tid] : -1;
-  __syncthreads();
+  float* s_m = reinterpret_cast<float*>(smem);     // [2 waves along the vocabulary][256 tokens]
+  float* s_s = s_m + 2 * BN;
 
-  const int wave_col0 = lp.wn * WAVE_N;                      // first column of this wave inside the tile
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+  for (int j = 0; j < TN; ++j) {
+    const int tok = lp.col(j);
+    const int y = (tok < rowsT) ? a.targets[t0 + tok] : -1;
+    const int yrow = y - (int)v0;                    // vocab row of the target inside this tile (if 0 <= . < rowsV)
+    float m = -INFINITY, zy = 0.f;
+    bool mine = false;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int rib = lp.row(i, r);
-      float v[TN];
-      float m = -INFINITY;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        v[j] = (lp.col(j) < rowsB) ? acc[i][j][r] : -INFINITY;
-        m = fmaxf(m, v[j]);
+      for (int r = 0; r < 16; ++r) {
+        const int vr = lp.row(i, r);
+        const float z = acc[i][j][r];
+        if (vr < rowsV) m = fmaxf(m, z);
+        if (vr == yrow) { zy = z; mine = true; }
       }
-      m = half_wave_max(m);
-      const float m_safe = (m == -INFINITY) ? 0.f : m;
-      float s = 0.f;
+    m = fmaxf(m, __shfl_xor(m, 32));
+    const float mb = (m == -INFINITY) ? 0.f : m * LOG2E;
+    float s = 0.f;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) s += __expf(v[j] - m_safe);   // exp(-inf) = 0 for padded columns
-      s = half_wave_sum(s);
-      // target logit: at most one lane of one wave of one tile owns column y_t of this row
-      const int t = s_tgt[rib] - (int)col0 - wave_col0;
-      if (t >= 0 && t < WAVE_N && (t & 31) == (lp.lane & 31) && rib < rowsA && t + wave_col0 < rowsB) {
-        float z = acc[i][0][r];
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 1; j < TN; ++j)
-          if ((t >> 5) == j) z = acc[i][j][r];
-        a.zt[row0 + rib] = z;
+      for (int r = 0; r < 16; ++r) {
+        const float e = exp2f(fmaf(acc[i][j][r], LOG2E, -mb));
+        s += (lp.row(i, r) < rowsV) ? e : 0.f;
       }
-      if ((lp.lane & 31) == 0) {
-        s_m[lp.wn * BM + rib] = m;
-        s_s[lp.wn * BM + rib] = s;
-      }
+    s += __shfl_xor(s, 32);
+    if (mine && y >= 0 && yrow < rowsV && tok < rowsT) a.zt[t0 + tok] = zy;
+    if ((lp.lane >> 5) == 0) {
+      s_m[lp.wm * BN + tok] = m;
+      s_s[lp.wm * BN + tok] = s;
     }
   }
   __syncthreads();
-  if (tid < rowsA) {
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < WAVES_N; ++w) M = fmaxf(M, s_m[w * BM + tid]);
-    const float M_safe = (M == -INFINITY) ? 0.f : M;
-    float S = 0.f;
-#pragma unroll
-    for (int w = 0; w < WAVES_N; ++w) S += s_s[w * BM + tid] * __expf(s_m[w * BM + tid] - M_safe);
-    a.part_m[(int64_t)tn * a.n_pad + row0 + tid] = M;
-    a.part_s[(int64_t)tn * a.n_pad + row0 + tid] = S;
+  if (tid < rowsT) {
+    const float m0 = s_m[tid], m1 = s_m[BN + tid];
+    const float M = fmaxf(m0, m1);
+    const float Mb = (M == -INFINITY) ? 0.f : M;
+    const float S = s_s[tid] * __expf(m0 - Mb) + s_s[BN + tid] * __expf(m1 - Mb);
+    a.part_m[(int64_t)tv * a.n_pad + t0 + tid] = M;
+    a.part_s[(int64_t)tv * a.n_pad + t0 + tid] = S;
   }
 }
 
 // lse[t] = log sum over vocab tiles; logp[t] = z[t,y_t] - lse[t]; masked / bad-target rows -> 0 (a select).
-__global__ void k_merge_logp(const float* part_m, const float* part_s, const float* zt, const int32_t* targets,
-                             const uint8_t* mask, int64_t N, int64_t V, int tiles_n, int64_t n_pad, float* logp,
-                             float* lse) {
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= N) return;
-  const int y = targets[t];
-  const bool valid = (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
-  if (!valid) {
-    logp[t] = 0.f;
-    lse[t] = 0.f;
-    return;
+// 256 threads = 64 tokens x 4 slices of the vocab-tile list.
+__global__ __launch_bounds__(256) void k_merge_logp(const float* part_m, const float* part_s, const float* zt,
+                                                     const int32_t* targets, const uint8_t* mask, int64_t N,
+                                                     int64_t V, int tiles_v, int64_t n_pad, float* logp,
+                                                     float* lse) {
+  __shared__ float s_M[4][64], s_S[4][64];
+  const int tok = threadIdx.x & 63, sl = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * 64 + tok;
+  float M = -INFINITY, S = 0.f;
+  if (t < N) {
+    for (int j = sl; j < tiles_v; j += 4) {
+      const float m = part_m[(int64_t)j * n_pad + t], s = part_s[(int64_t)j * n_pad + t];
+      if (m > M) {
+        S = S * __expf(M - m) + s;      // exp(-inf) = 0 on the first tile
+        M = m;
+      } else if (m != -INFINITY) {
+        S += s * __expf(m - M);
+      }
+    }
   }
-  float M = -INFINITY;
-  for (int j = 0; j < tiles_n; ++j) M = fmaxf(M, part_m[(int64_t)j * n_pad + t]);
-  float S = 0.f;
-  for (int j = 0; j < tiles_n; ++j) S += part_s[(int64_t)j * n_pad + t] * expf(part_m[(int64_t)j * n_pad + t] - M);
-  const float l = M + logf(S);
-  lse[t] = l;
-  logp[t] = zt[t] - l;
+  s_M[sl][tok] = M;
+  s_S[sl][tok] = S;
+  __syncthreads();
+  if (sl == 0 && t < N) {
+    const int y = targets[t];
+    const bool valid = (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
+    float l = 0.f, lp = 0.f;
+    if (valid) {
+      float Mx = s_M[0][tok];
+#pragma unroll
+      for (int q = 1; q < 4; ++q) Mx = fmaxf(Mx, s_M[q][tok]);
+      float Sx = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) Sx += (s_M[q][tok] == -INFINITY) ? 0.f : s_S[q][tok] * expf(s_M[q][tok] - Mx);
+      l = Mx + logf(Sx);
+      lp = zt[t] - l;
+    }
+    lse[t] = l;
+    logp[t] = lp;
+  }
 }
 
 struct DzArgs {
@@ -145,108 +152,102 @@ struct DzArgs {
   const float* coef;
   float g;
   int64_t N, d, V;
-  int tiles_m, tiles_n;
-  void* dz;     // [N][ldz]   (type of H/W); columns V..ldz-1 written as zero
+  int tiles_v, tiles_t;
+  void* dz;     // [N][ldz]  token-major (type of H/W); columns V..ldz-1 written as zero
   int64_t ldz;
-  void* dzt;    // [V][ldzt]; columns N..ldzt-1 written as zero
+  void* dzt;    // [V][ldzt] vocab-major; columns N..ldzt-1 written as zero
   int64_t ldzt;
 };
 
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int tm, tn;
-  tile_coords(a.tiles_m, a.tiles_n, tm, tn);
-  const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-  const int rowsA = (int)min((int64_t)BM, a.N - row0);
-  const int rowsB = (int)min((int64_t)BN, a.V - col0);
+  int tv, tt;
+  tile_coords(a.tiles_v, a.tiles_t, tv, tt);
+  const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
+  const int rowsV = (int)min((int64_t)BM, a.V - v0);
+  const int rowsT = (int)min((int64_t)BN, a.N - t0);
   typedef typename TT::store_t st;
   f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.H + row0 * a.d, a.d, rowsA, (const st*)a.W + col0 * a.d, a.d, rowsB, a.d, smem,
-                       acc);
+  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, (const st*)a.H + t0 * a.d, a.d, rowsT, a.d, smem, acc);
 
   const int tid = threadIdx.x;
   LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
-  __syncthreads();
-  int* s_tgt = reinterpret_cast<int*>(smem);                 // [256]
-  float* s_lse = reinterpret_cast<float*>(smem + 1024);      // [256]
-  float* s_cg = reinterpret_cast<float*>(smem + 2048);       // [256]
-  if (tid < BM) {
-    const bool in = tid < rowsA;
-    const float c = in ? a.g * a.coef[row0 + tid] : 0.f;
-    s_tgt[tid] = in ? a.targets[row0 + tid] : -1;
-    s_cg[tid] = c;
-    s_lse[tid] = (c != 0.f) ? a.lse[row0 + tid] : 0.f;
-  }
-  __syncthreads();
 
-  // dz in place of the logits
+  // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    __builtin_amdgcn_sched_barrier(0);   // keep the unrolled blocks apart: bounds live registers
+  for (int j = 0; j < TN; ++j) {
+    const int tok = lp.col(j);
+    const bool in = tok < rowsT;
+    const float c = in ? a.g * a.coef[t0 + tok] : 0.f;
+    const float lb = (c != 0.f) ? a.lse[t0 + tok] * LOG2E : 0.f;
+    const int yrow = (in ? a.targets[t0 + tok] : -1) - (int)v0;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int rib = lp.row(i, r);
-      const float c = s_cg[rib], l = s_lse[rib];
-      const int t = s_tgt[rib] - (int)col0;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int cib = lp.col(j);
-        const float p = __expf(acc[i][j][r] - l);
-        const float dzv = c * (((cib == t) ? 1.f : 0.f) - p);
-        acc[i][j][r] = (c != 0.f && cib < rowsB) ? dzv : 0.f;   // select: masked rows / padded columns are 0
+      for (int r = 0; r < 16; ++r) {
+        const int vr = lp.row(i, r);
+        const float p = exp2f(fmaf(acc[i][j][r], LOG2E, -lb));
+        const float dzv = c * (((vr == yrow) ? 1.f : 0.f) - p);
+        acc[i][j][r] = (c != 0.f && vr < rowsV) ? dzv : 0.f;   // select: masked tokens / padded vocab rows are 0
       }
-    }
   }
 
   // how far the zero padding of each orientation reaches inside this tile
-  const int dz_cols = (int)min((int64_t)BN, a.ldz - col0);     // dz[row][col]: rows < N, cols < ldz
-  const int dzt_cols = (int)min((int64_t)BM, a.ldzt - row0);   // dzt[col][row]: cols < V, rows < ldzt
+  const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
+  const int dz_cols = (int)min((int64_t)BM, a.ldz - v0);     // dz[token][vocab]:  token < N, vocab < ldz
 
   if constexpr (sizeof(st) == 2) {
-    uint16_t* stage = reinterpret_cast<uint16_t*>(smem + EPI_LDS_HEADER);
-    // orientation 1: stage[row][col]
+    // bf16: pack pairs of consecutive vocab rows first (the fp32 values die here), then stage each orientation
+    // through LDS so that global stores are full 16-byte chunks of contiguous rows.
+    uint32_t pk[TM][TN][8];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) stage[lp.row(i, r) * STAGE_LD + lp.col(j)] = float_to_bf16_bits(acc[i][j][r]);
-      }
+        for (int p = 0; p < 8; ++p) pk[i][j][p] = pack_bf16(acc[i][j][2 * p], acc[i][j][2 * p + 1]);
+    __syncthreads();                                         // main-loop LDS reads are over: reuse smem
+    uint16_t* stage = reinterpret_cast<uint16_t*>(smem);
+    // token-major: stage[token][vocab]; a lane holds 4 consecutive vocab rows of one token = 8 bytes
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          uint2 v;
+          v.x = pk[i][j][2 * q4];
+          v.y = pk[i][j][2 * q4 + 1];
+          *reinterpret_cast<uint2*>(stage + lp.col(j) * STAGE_LD + lp.row(i, q4 * 4)) = v;
+        }
     __syncthreads();
     uint16_t* dz = reinterpret_cast<uint16_t*>(a.dz);
-    for (int q = tid; q < BM * (BN / 8); q += NTHREADS) {
-      const int row = q >> 5, ch = q & 31;
-      if (row < rowsA && ch * 8 < dz_cols) {
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * STAGE_LD + ch * 8);
-        *reinterpret_cast<uint4*>(dz + (row0 + row) * a.ldz + col0 + ch * 8) = v;
+    for (int q = tid; q < BN * (BM / 8); q += NTHREADS) {
+      const int tok = q >> 5, ch = q & 31;
+      if (tok < rowsT && ch * 8 < dz_cols) {
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + tok * STAGE_LD + ch * 8);
+        *reinterpret_cast<uint4*>(dz + (t0 + tok) * a.ldz + v0 + ch * 8) = v;
       }
     }
     __syncthreads();
-    // orientation 2: stage[col][row]; a lane holds 4 consecutive rows of one column
+    // vocab-major: stage[vocab][token]; lanes of a half-wave hold 32 consecutive tokens
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          uint2 pk;
-          pk.x = (uint32_t)float_to_bf16_bits(acc[i][j][q4 * 4 + 0]) |
-                 ((uint32_t)float_to_bf16_bits(acc[i][j][q4 * 4 + 1]) << 16);
-          pk.y = (uint32_t)float_to_bf16_bits(acc[i][j][q4 * 4 + 2]) |
-                 ((uint32_t)float_to_bf16_bits(acc[i][j][q4 * 4 + 3]) << 16);
-          *reinterpret_cast<uint2*>(stage + lp.col(j) * STAGE_LD + lp.row(i, q4 * 4)) = pk;
+        for (int p = 0; p < 8; ++p) {
+          stage[lp.row(i, 2 * p) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] & 0xffffu);
+          stage[lp.row(i, 2 * p + 1) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] >> 16);
         }
-      }
     __syncthreads();
     uint16_t* dzt = reinterpret_cast<uint16_t*>(a.dzt);
-    for (int q = tid; q < BN * (BM / 8); q += NTHREADS) {
-      const int col = q >> 5, ch = q & 31;
-      if (col < rowsB && ch * 8 < dzt_cols) {
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + col * STAGE_LD + ch * 8);
-        *reinterpret_cast<uint4*>(dzt + (col0 + col) * a.ldzt + row0 + ch * 8) = v;
+    for (int q = tid; q < BM * (BN / 8); q += NTHREADS) {
+      const int vr = q >> 5, ch = q & 31;
+      if (vr < rowsV && ch * 8 < dzt_cols) {
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + vr * STAGE_LD + ch * 8);
+        *reinterpret_cast<uint4*>(dzt + (v0 + vr) * a.ldzt + t0 + ch * 8) = v;
       }
     }
   } else {
@@ -258,9 +259,9 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int rib = lp.row(i, r), cib = lp.col(j);
-          if (rib < rowsA && cib < dz_cols) dz[(row0 + rib) * a.ldz + col0 + cib] = acc[i][j][r];
-          if (cib < rowsB && rib < dzt_cols) dzt[(col0 + cib) * a.ldzt + row0 + rib] = acc[i][j][r];
+          const int vr = lp.row(i, r), tok = lp.col(j);
+          if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = acc[i][j][r];
+          if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = acc[i][j][r];
         }
   }
 }

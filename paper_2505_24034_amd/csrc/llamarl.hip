@@ -32,16 +32,16 @@ inline size_t esize(llamarl_dtype dt) { return dt == LLAMARL_BF16 ? 2 : 4; }
 
 // ---- workspace layouts (every block 256-byte aligned) ----------------------------------------------------
 struct FwdWs {
-  int tiles_m, tiles_n;
+  int tiles_v, tiles_t;
   int64_t n_pad;
   size_t off_m, off_s, off_zt, total;
 };
 FwdWs fwd_ws(int64_t N, int64_t V) {
   FwdWs w;
-  w.tiles_m = (int)((N + BM - 1) / BM);
-  w.tiles_n = (int)((V + BN - 1) / BN);
-  w.n_pad = round_up(N, BM);
-  const size_t plane = (size_t)w.tiles_n * (size_t)w.n_pad * sizeof(float);
+  w.tiles_v = (int)((V + BM - 1) / BM);
+  w.tiles_t = (int)((N + BN - 1) / BN);
+  w.n_pad = round_up(N, BN);
+  const size_t plane = (size_t)w.tiles_v * (size_t)w.n_pad * sizeof(float);
   w.off_m = 0;
   w.off_s = round_up((int64_t)plane, 256);
   w.off_zt = w.off_s + round_up((int64_t)plane, 256);
@@ -130,15 +130,15 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
   const FwdWs w = fwd_ws(N, V);
   FwdArgs a;
   a.H = H; a.W = W; a.targets = targets; a.N = N; a.d = d; a.V = V;
-  a.tiles_m = w.tiles_m; a.tiles_n = w.tiles_n; a.n_pad = w.n_pad;
+  a.tiles_v = w.tiles_v; a.tiles_t = w.tiles_t; a.n_pad = w.n_pad;
   a.part_m = reinterpret_cast<float*>(ws + w.off_m);
   a.part_s = reinterpret_cast<float*>(ws + w.off_s);
   a.zt = reinterpret_cast<float*>(ws + w.off_zt);
   HIP_TRY(set_lds(k_fwd_partials<TT>, MAINLOOP_LDS_BYTES));
-  k_fwd_partials<TT><<<dim3((unsigned)(w.tiles_m * w.tiles_n)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
+  k_fwd_partials<TT><<<dim3((unsigned)(w.tiles_v * w.tiles_t)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
   HIP_TRY(hipGetLastError());
-  k_merge_logp<<<dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, targets, mask, N, V,
-                                                                       w.tiles_n, w.n_pad, logp, lse);
+  k_merge_logp<<<dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, targets, mask, N, V,
+                                                                     w.tiles_v, w.n_pad, logp, lse);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
@@ -165,13 +165,12 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   // recompute logits tile by tile, turn them into dz in both orientations
   DzArgs a;
   a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
-  a.tiles_m = (int)((N + BM - 1) / BM);
-  a.tiles_n = (int)((V + BN - 1) / BN);
+  a.tiles_v = (int)((V + BM - 1) / BM);
+  a.tiles_t = (int)((N + BN - 1) / BN);
   a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt;
-  const int dz_lds = sizeof(stt) == 2 ? (DZ_LDS_BYTES > MAINLOOP_LDS_BYTES ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES)
-                                      : MAINLOOP_LDS_BYTES;
+  const int dz_lds = sizeof(stt) == 2 ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES;
   HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
-  k_bwd_dz<TT><<<dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(NTHREADS), dz_lds, st>>>(a);
+  k_bwd_dz<TT><<<dim3((unsigned)(a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
   HIP_TRY(hipGetLastError());
 
   // dH [N,d] = dz [N,V] . W^T[d,V]^T      (K = V, zero-padded to ldz)
