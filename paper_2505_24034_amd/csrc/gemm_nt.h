@@ -86,14 +86,17 @@ struct LanePos {
   __device__ __forceinline__ int col(int j) const { return wn * WAVE_N + j * 32 + (lane & 31); }
 };
 
-// blockIdx -> (tile_m, tile_n).  Workgroups are dealt round-robin to the 8 XCDs, each with a private L2: give
-// every XCD a contiguous run of tile ids, and order ids so that 32 consecutive ones form an 8 x 4 patch that
-// shares A and B panels.
-__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
-  const int nblk = gridDim.x;
+// blockIdx -> (tile_m, tile_n), or false if this block has no tile.  The grid is sized on the host for the
+// worst case; tiles_m x tiles_n is the number of tiles that exist once the device-side active-row count is known.
+// Workgroups are dealt round-robin to the 8 XCDs, each with a private L2: every XCD gets a contiguous, equally
+// long run of tile ids, and ids are ordered so that 32 consecutive ones form an 8 x 4 patch sharing A and B panels.
+__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int nact = tiles_m * tiles_n;
   const int bid = blockIdx.x;
   const int xcd = bid & 7, local = bid >> 3;
-  const int id = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
+  const int base = nact >> 3, rem = nact & 7;
+  if (local >= base + (xcd < rem ? 1 : 0)) return false;
+  const int id = xcd * base + min(xcd, rem) + local;
   constexpr int GROUP_M = 8;
   const int per_group = GROUP_M * tiles_n;
   const int g = id / per_group;
@@ -102,6 +105,7 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, i
   const int in_g = id - g * per_group;
   tm = first_m + in_g % gsize;
   tn = in_g / gsize;
+  return true;
 }
 
 __device__ __forceinline__ int swizzle(int row) { return (row >> 1) & 7; }
@@ -127,6 +131,23 @@ struct SlabLoader {
       lds_row0[it] = r0;
       chunk_k[it] = (uint32_t)(c * TT::EPC);
       voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + (uint32_t)c * 16u : OOB_OFFSET;
+    }
+  }
+  // Gathered panel: tile row r is row rows[r] of the whole matrix `base` (total_rows rows, < 2^31 bytes).
+  // Free with per-lane buffer offsets: this is how masked tokens are skipped without a packed copy of H.
+  __device__ __forceinline__ void init_gather(const void* base, int64_t ld, int64_t total_rows, const int32_t* rows,
+                                              int rows_valid, int wave, int lane) {
+    const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
+    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)((uint32_t)total_rows * row_bytes),
+                                             0x00020000);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int r0 = (it * 8 + wave) * 8;
+      const int row = r0 + (lane >> 3);
+      const int c = (lane & 7) ^ swizzle(row);
+      lds_row0[it] = r0;
+      chunk_k[it] = (uint32_t)(c * TT::EPC);
+      voff[it] = (row < rows_valid) ? (uint32_t)rows[row] * row_bytes + (uint32_t)c * 16u : OOB_OFFSET;
     }
   }
   // k0: first k of the slab (elements); K: contraction length.  lds: start of this operand's slab in LDS.
@@ -187,10 +208,14 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
 //   sync   : wait for this thread's share of slab kt+1, barrier (slab kt+1 visible, slab kt no longer read)
 //   issue  : slab kt+2 -> the buffer slab kt just vacated
 //   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1
+//
+// b_rows != nullptr: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
+// tile row r is its row b_rows[r].
 template <typename TT>
 __device__ __forceinline__ void gemm_nt_mainloop(const void* A_tile, int64_t lda, int rowsA, const void* B_tile,
                                                  int64_t ldb, int rowsB, int64_t K, char* smem,
-                                                 f32x16_t (&acc)[TM][TN]) {
+                                                 f32x16_t (&acc)[TM][TN], const int32_t* b_rows = nullptr,
+                                                 int64_t b_total = 0) {
   typedef typename TT::frag_t frag_t;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -198,7 +223,8 @@ __device__ __forceinline__ void gemm_nt_mainloop(const void* A_tile, int64_t lda
 
   SlabLoader<TT> la, lb;
   la.init(A_tile, lda, rowsA, wave, lane);
-  lb.init(B_tile, ldb, rowsB, wave, lane);
+  if (b_rows != nullptr) lb.init_gather(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
+  else lb.init(B_tile, ldb, rowsB, wave, lane);
 
 #pragma unroll
   for (int i = 0; i < TM; ++i)

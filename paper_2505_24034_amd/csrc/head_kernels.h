@@ -22,6 +22,9 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// v_exp_f32 without the denormal-range fix-up of exp2f(): arguments here are <= 0 up to rounding, results that
+// underflow are exact zeros in the sums they feed.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // v_cvt_pk_bf16_f32: round to nearest even
   f32x2_t v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
@@ -37,19 +40,22 @@ struct FwdArgs {
   float* part_m;          // [tiles_v][n_pad] max of the tile's logits of a token
   float* part_s;          // [tiles_v][n_pad] sum of exp(logit - max)
   float* zt;              // [n_pad] target logit, written by the one tile that holds vocab row y_t
-};
+  const int32_t* rows;    // [n_act] active token rows, ascending: position p of the compacted list is token rows[p]
+  const int32_t* n_act;   // device scalar
+};  // partials and zt are indexed by compacted position, not by token
 
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int tv, tt;
-  tile_coords(a.tiles_v, a.tiles_t, tv, tt);
+  const int n_act = *a.n_act;
+  if (!tile_coords(a.tiles_v, (n_act + BN - 1) / BN, tv, tt)) return;   // block-uniform: token tiles of masked rows
   const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
   const int rowsV = (int)min((int64_t)BM, a.V - v0);
-  const int rowsT = (int)min((int64_t)BN, a.N - t0);
+  const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
   typedef typename TT::store_t st;
   f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, (const st*)a.H + t0 * a.d, a.d, rowsT, a.d, smem, acc);
+  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, a.H, a.d, rowsT, a.d, smem, acc, a.rows + t0, a.N);
 
   const int tid = threadIdx.x;
   LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
@@ -57,21 +63,29 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   float* s_m = reinterpret_cast<float*>(smem);     // [2 waves along the vocabulary][256 tokens]
   float* s_s = s_m + 2 * BN;
 
+  if (rowsV < BM) {   // last vocab tile only (block-uniform): rows past V must not enter the softmax
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (lp.row(i, r) >= rowsV) acc[i][j][r] = -INFINITY;
+  }
+  const int lane_row0 = lp.row(0, 0);                // rows of this lane: lane_row0 + i*32 + (r/4)*8 + r%4
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int tok = lp.col(j);
-    const int y = (tok < rowsT) ? a.targets[t0 + tok] : -1;
+    const int y = (tok < rowsT) ? a.targets[a.rows[t0 + tok]] : -1;
     const int yrow = y - (int)v0;                    // vocab row of the target inside this tile (if 0 <= . < rowsV)
+    const int yrel = yrow - lane_row0;               // ... relative to this lane's first row
     float m = -INFINITY, zy = 0.f;
-    bool mine = false;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int vr = lp.row(i, r);
-        const float z = acc[i][j][r];
-        if (vr < rowsV) m = fmaxf(m, z);
-        if (vr == yrow) { zy = z; mine = true; }
+        m = fmaxf(m, acc[i][j][r]);
+        zy = (yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? acc[i][j][r] : zy;
       }
     m = fmaxf(m, __shfl_xor(m, 32));
     const float mb = (m == -INFINITY) ? 0.f : m * LOG2E;
@@ -79,11 +93,9 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = exp2f(fmaf(acc[i][j][r], LOG2E, -mb));
-        s += (lp.row(i, r) < rowsV) ? e : 0.f;
-      }
+      for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[i][j][r], LOG2E, -mb));   // exp2(-inf) = 0
     s += __shfl_xor(s, 32);
+    const bool mine = yrel >= 0 && yrel < WAVE_M && (yrel & 4) == 0;                   // one of this lane's rows
     if (mine && y >= 0 && yrow < rowsV && tok < rowsT) a.zt[t0 + tok] = zy;
     if ((lp.lane >> 5) == 0) {
       s_m[lp.wm * BN + tok] = m;
@@ -101,19 +113,20 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   }
 }
 
-// lse[t] = log sum over vocab tiles; logp[t] = z[t,y_t] - lse[t]; masked / bad-target rows -> 0 (a select).
-// 256 threads = 64 tokens x 4 slices of the vocab-tile list.
+// lse[t] = log sum over vocab tiles; logp[t] = z[t,y_t] - lse[t], for the active tokens (the compaction pass
+// already wrote 0 for masked / bad-target rows).  256 threads = 64 list positions x 4 slices of the vocab tiles.
 __global__ __launch_bounds__(256) void k_merge_logp(const float* part_m, const float* part_s, const float* zt,
-                                                     const int32_t* targets, const uint8_t* mask, int64_t N,
-                                                     int64_t V, int tiles_v, int64_t n_pad, float* logp,
-                                                     float* lse) {
+                                                     const int32_t* rows, const int32_t* n_act, int tiles_v,
+                                                     int64_t n_pad, float* logp, float* lse) {
   __shared__ float s_M[4][64], s_S[4][64];
   const int tok = threadIdx.x & 63, sl = threadIdx.x >> 6;
-  const int64_t t = (int64_t)blockIdx.x * 64 + tok;
+  const int64_t p = (int64_t)blockIdx.x * 64 + tok;
+  const int64_t n = *n_act;
+  if ((int64_t)blockIdx.x * 64 >= n) return;        // block-uniform
   float M = -INFINITY, S = 0.f;
-  if (t < N) {
+  if (p < n) {
     for (int j = sl; j < tiles_v; j += 4) {
-      const float m = part_m[(int64_t)j * n_pad + t], s = part_s[(int64_t)j * n_pad + t];
+      const float m = part_m[(int64_t)j * n_pad + p], s = part_s[(int64_t)j * n_pad + p];
       if (m > M) {
         S = S * __expf(M - m) + s;      // exp(-inf) = 0 on the first tile
         M = m;
@@ -125,23 +138,72 @@ __global__ __launch_bounds__(256) void k_merge_logp(const float* part_m, const f
   s_M[sl][tok] = M;
   s_S[sl][tok] = S;
   __syncthreads();
-  if (sl == 0 && t < N) {
-    const int y = targets[t];
-    const bool valid = (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
-    float l = 0.f, lp = 0.f;
-    if (valid) {
-      float Mx = s_M[0][tok];
+  if (sl == 0 && p < n) {
+    float Mx = s_M[0][tok];
 #pragma unroll
-      for (int q = 1; q < 4; ++q) Mx = fmaxf(Mx, s_M[q][tok]);
-      float Sx = 0.f;
+    for (int q = 1; q < 4; ++q) Mx = fmaxf(Mx, s_M[q][tok]);
+    float Sx = 0.f;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) Sx += (s_M[q][tok] == -INFINITY) ? 0.f : s_S[q][tok] * expf(s_M[q][tok] - Mx);
-      l = Mx + logf(Sx);
-      lp = zt[t] - l;
-    }
+    for (int q = 0; q < 4; ++q) Sx += (s_M[q][tok] == -INFINITY) ? 0.f : s_S[q][tok] * expf(s_M[q][tok] - Mx);
+    const float l = Mx + logf(Sx);
+    const int64_t t = rows[p];
     lse[t] = l;
-    logp[t] = lp;
+    logp[t] = zt[p] - l;
   }
+}
+
+// Active-row list.  mode 0 (forward): row t is active if mask[t] != 0 (mask == nullptr: always) and its target
+// is inside [0,V); inactive rows get logp = lse = 0 here.  mode 1 (backward): active if coef[t] != 0.
+// One block: an ordered scan keeps the list ascending, so every later kernel is deterministic.
+__global__ __launch_bounds__(1024) void k_compact_rows(int mode, const uint8_t* mask, const int32_t* targets,
+                                                        int64_t V, const float* coef, int64_t N, int32_t* rows,
+                                                        int32_t* n_act, float* logp, float* lse) {
+  __shared__ int s_wave[16];
+  __shared__ int s_base;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_base = 0;
+  __syncthreads();
+  for (int64_t start = 0; start < N; start += 1024) {
+    const int64_t t = start + tid;
+    bool act = false;
+    if (t < N) {
+      if (mode == 0) {
+        const int y = targets[t];
+        act = (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
+        if (!act) {
+          logp[t] = 0.f;
+          lse[t] = 0.f;
+        }
+      } else {
+        act = coef[t] != 0.f;
+      }
+    }
+    const unsigned long long b = __ballot(act);
+    const int before = __popcll(b & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wave[wave] = __popcll(b);
+    __syncthreads();
+    int off = s_base;
+    for (int w = 0; w < wave; ++w) off += s_wave[w];
+    if (act) rows[off + before] = (int32_t)t;
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+      for (int w = 0; w < 16; ++w) tot += s_wave[w];
+      s_base += tot;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) *n_act = s_base;
+}
+
+// dH rows of inactive tokens (coef == 0) are exactly zero; the dH contraction only writes the active ones.
+template <typename ST>
+__global__ __launch_bounds__(256) void k_zero_inactive_rows(ST* dH, const float* coef, int64_t N, int64_t d) {
+  const int64_t t = blockIdx.x;
+  if (coef[t] != 0.f) return;
+  uint4* p = reinterpret_cast<uint4*>(dH + t * d);
+  const int64_t n16 = d * (int64_t)sizeof(ST) / 16;
+  for (int64_t i = threadIdx.x; i < n16; i += 256) p[i] = make_uint4(0, 0, 0, 0);
 }
 
 struct DzArgs {
@@ -157,40 +219,54 @@ struct DzArgs {
   int64_t ldz;
   void* dzt;    // [V][ldzt] vocab-major; columns N..ldzt-1 written as zero
   int64_t ldzt;
+  const int32_t* rows;    // active token rows (coef != 0), ascending; dz / dzt are indexed by list position
+  const int32_t* n_act;
 };
 
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int tv, tt;
-  tile_coords(a.tiles_v, a.tiles_t, tv, tt);
+  const int n_act = *a.n_act;
+  if (!tile_coords(a.tiles_v, (n_act + BN - 1) / BN, tv, tt)) return;   // block-uniform: no active token there
   const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
   const int rowsV = (int)min((int64_t)BM, a.V - v0);
-  const int rowsT = (int)min((int64_t)BN, a.N - t0);
+  const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
   typedef typename TT::store_t st;
   f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, (const st*)a.H + t0 * a.d, a.d, rowsT, a.d, smem, acc);
+  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, a.H, a.d, rowsT, a.d, smem, acc, a.rows + t0, a.N);
 
   const int tid = threadIdx.x;
   LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
 
   // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
+  const int lane_row0 = lp.row(0, 0);
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int tok = lp.col(j);
     const bool in = tok < rowsT;
-    const float c = in ? a.g * a.coef[t0 + tok] : 0.f;
-    const float lb = (c != 0.f) ? a.lse[t0 + tok] * LOG2E : 0.f;
-    const int yrow = (in ? a.targets[t0 + tok] : -1) - (int)v0;
+    const int64_t t = in ? a.rows[t0 + tok] : 0;
+    const float c = in ? a.g * a.coef[t] : 0.f;
+    const float lb = (c != 0.f) ? a.lse[t] * LOG2E : 0.f;
+    const int yrel = (in ? a.targets[t] : -1) - (int)v0 - lane_row0;
+    const bool live = c != 0.f;                              // select: a masked token's row is exactly 0
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int vr = lp.row(i, r);
-        const float p = exp2f(fmaf(acc[i][j][r], LOG2E, -lb));
-        const float dzv = c * (((vr == yrow) ? 1.f : 0.f) - p);
-        acc[i][j][r] = (c != 0.f && vr < rowsV) ? dzv : 0.f;   // select: masked tokens / padded vocab rows are 0
+        const float p = fast_exp2(fmaf(acc[i][j][r], LOG2E, -lb));
+        const float onehot = (yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? 1.f : 0.f;
+        acc[i][j][r] = live ? c * (onehot - p) : 0.f;
       }
+  }
+  if (rowsV < BM) {   // last vocab tile only (block-uniform): padded vocab rows are 0
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (lp.row(i, r) >= rowsV) acc[i][j][r] = 0.f;
   }
 
   // how far the zero padding of each orientation reaches inside this tile
@@ -272,27 +348,62 @@ struct StoreArgs {
   const void* B;
   int64_t ldb;
   int64_t M, Nn, K;
-  int tiles_m, tiles_n;
+  int tiles_n;
   void* C;
   int64_t ldc;
   int c_is_f32;
   int accumulate;
+  const int32_t* m_count;   // non-null: M = *m_count (device scalar)
+  const int32_t* k_count;   // non-null: K = *k_count rounded up to 64 (the operands are zero-padded that far)
+  const int32_t* c_rows;    // non-null: output row r goes to row c_rows[r] of C
+  int splits;               // > 1: split s contracts its share of the K slabs into the fp32 slice C + s * split_stride
+  int64_t split_stride;
 };
 
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int tm, tn;
-  tile_coords(a.tiles_m, a.tiles_n, tm, tn);
+  const int64_t M = a.m_count ? (int64_t)*a.m_count : a.M;
+  const int64_t K = a.k_count ? ((int64_t)*a.k_count + 63) / 64 * 64 : a.K;
+  const int tiles_m = (int)((M + BM - 1) / BM);
+  int tms, tn;
+  // split-major ids: all tiles of one K range run together and share operand panels in L2
+  if (!tile_coords(tiles_m * a.splits, a.tiles_n, tms, tn)) return;     // block-uniform
+  const int split = tms / tiles_m, tm = tms - split * tiles_m;
   const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-  const int rowsA = (int)min((int64_t)BM, a.M - row0);
+  const int rowsA = (int)min((int64_t)BM, M - row0);
   const int rowsB = (int)min((int64_t)BN, a.Nn - col0);
   typedef typename TT::store_t st;
+  constexpr int BK = 8 * TT::EPC;
+  const int64_t nk = (K + BK - 1) / BK;
+  const int64_t k_lo = nk * split / a.splits * BK, k_hi = min(K, nk * (split + 1) / a.splits * BK);
   f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.A + row0 * a.lda, a.lda, rowsA, (const st*)a.B + col0 * a.ldb, a.ldb, rowsB, a.K,
-                       smem, acc);
+  if (k_hi > k_lo) {
+    gemm_nt_mainloop<TT>((const st*)a.A + row0 * a.lda + k_lo, a.lda, rowsA, (const st*)a.B + col0 * a.ldb + k_lo,
+                         a.ldb, rowsB, k_hi - k_lo, smem, acc);
+  } else {                                           // nothing to contract: the product is zero
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  }
   const int tid = threadIdx.x;
   LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  if (a.splits > 1) {                                // fp32 partial slice, rows by list position
+    float* C = reinterpret_cast<float*>(a.C) + (int64_t)split * a.split_stride;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rib = lp.row(i, r), cib = lp.col(j);
+          if (rib < rowsA && cib < rowsB) C[(row0 + rib) * a.ldc + col0 + cib] = acc[i][j][r];
+        }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -301,7 +412,8 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
       for (int r = 0; r < 16; ++r) {
         const int rib = lp.row(i, r), cib = lp.col(j);
         if (rib < rowsA && cib < rowsB) {
-          const int64_t idx = (row0 + rib) * a.ldc + col0 + cib;
+          const int64_t crow = a.c_rows ? (int64_t)a.c_rows[row0 + rib] : row0 + rib;
+          const int64_t idx = crow * a.ldc + col0 + cib;
           float v = acc[i][j][r];
           if (a.c_is_f32) {
             float* C = reinterpret_cast<float*>(a.C);
@@ -316,18 +428,46 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
       }
 }
 
-// out[c][r] = keep(r) ? in[r][c] : 0 for r < R, c < C; out[c][r] = 0 for R <= r < ld_out.
-// keep(r) = (row_gate == nullptr || row_gate[r] != 0): rows whose gradient weight is zero must not leak NaNs.
+// out[rows[p]][c] = sum over splits (ascending) of part[s][p][c], p < *m_count; 4 columns per thread.
+template <typename ST>
+__global__ __launch_bounds__(256) void k_reduce_splits(const float* part, int splits, int64_t split_stride,
+                                                        const int32_t* rows, const int32_t* m_count, int64_t ncols,
+                                                        ST* out, int64_t ldo) {
+  const int64_t p = blockIdx.x;
+  if (p >= (int64_t)*m_count) return;
+  const int64_t orow = rows ? (int64_t)rows[p] : p;
+  for (int64_t c = (int64_t)threadIdx.x * 4; c < ncols; c += 256 * 4) {
+    float4 s = *reinterpret_cast<const float4*>(part + p * ncols + c);
+    for (int q = 1; q < splits; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)q * split_stride + p * ncols + c);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    if constexpr (sizeof(ST) == 4) {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + orow * ldo + c) = s;
+    } else {
+      uint2 o;
+      o.x = pack_bf16(s.x, s.y);
+      o.y = pack_bf16(s.z, s.w);
+      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + orow * ldo + c) = o;
+    }
+  }
+}
+
+// out[c][p] = in[src(p)][c] for p < R, c < C; out[c][p] = 0 for R <= p < ld_out.
+// rows == nullptr: src(p) = p and R is the host value.  Otherwise src(p) = rows[p], R = *r_count, and only the
+// first R rounded up to 64 columns of `out` are written (the contraction that reads it stops there).
 template <typename ST>
 __global__ void k_transpose(const ST* in, int64_t R, int64_t C, int64_t ld_in, ST* out, int64_t ld_out,
-                            const float* row_gate) {
+                            const int32_t* rows, const int32_t* r_count) {
   __shared__ ST tile[64][65];
+  if (rows != nullptr) R = *r_count;
   const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
+  if (rows != nullptr && r0 >= R) return;                     // block-uniform
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;     // 256 threads: 64 x 4
   for (int rr = ty; rr < 64; rr += 4) {
     const int64_t r = r0 + rr, c = c0 + tx;
     ST v = 0;
-    if (r < R && c < C && (row_gate == nullptr || row_gate[r] != 0.f)) v = in[r * ld_in + c];
+    if (r < R && c < C) v = in[(rows ? (int64_t)rows[r] : r) * ld_in + c];
     tile[rr][tx] = v;
   }
   __syncthreads();

@@ -34,7 +34,7 @@ inline size_t esize(llamarl_dtype dt) { return dt == LLAMARL_BF16 ? 2 : 4; }
 struct FwdWs {
   int tiles_v, tiles_t;
   int64_t n_pad;
-  size_t off_m, off_s, off_zt, total;
+  size_t off_m, off_s, off_zt, off_rows, off_nact, total;
 };
 FwdWs fwd_ws(int64_t N, int64_t V) {
   FwdWs w;
@@ -45,7 +45,9 @@ FwdWs fwd_ws(int64_t N, int64_t V) {
   w.off_m = 0;
   w.off_s = round_up((int64_t)plane, 256);
   w.off_zt = w.off_s + round_up((int64_t)plane, 256);
-  w.total = w.off_zt + (size_t)round_up(w.n_pad * (int64_t)sizeof(float), 256);
+  w.off_rows = w.off_zt + (size_t)round_up(w.n_pad * (int64_t)sizeof(float), 256);
+  w.off_nact = w.off_rows + (size_t)round_up(w.n_pad * (int64_t)sizeof(int32_t), 256);
+  w.total = w.off_nact + 256;
   return w;
 }
 
@@ -65,7 +67,8 @@ LossWs loss_ws(int64_t N) {  // sized for the worst case B = N
 
 struct BwdWs {
   int64_t ldz, ldzt;  // padded leading dimensions (elements): V and N rounded up to 64
-  size_t off_dz, off_dzt, off_wt, off_ht, total;
+  size_t off_dz, off_dzt, off_wt, off_ht, off_rows, off_nact, off_part, total;
+  int dh_splits;      // K splits of the dH contraction (1 = none)
 };
 BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
   BwdWs w;
@@ -76,7 +79,16 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
   w.off_dzt = w.off_dz + (size_t)round_up(N * w.ldz * (int64_t)es, 256);
   w.off_wt = w.off_dzt + (size_t)round_up(V * w.ldzt * (int64_t)es, 256);
   w.off_ht = w.off_wt + (size_t)round_up(d * w.ldz * (int64_t)es, 256);
-  w.total = w.off_ht + (size_t)round_up(d * w.ldzt * (int64_t)es, 256);
+  w.off_rows = w.off_ht + (size_t)round_up(d * w.ldzt * (int64_t)es, 256);
+  w.off_nact = w.off_rows + (size_t)round_up(w.ldzt * (int64_t)sizeof(int32_t), 256);
+  w.off_part = w.off_nact + 256;
+  // dH has few output tiles (N/256 x d/256) with a very long K = V: split K until there are enough work items
+  // to fill 256 CUs evenly whatever the number of active rows turns out to be.  d % 4 keeps float4 rows.
+  const int64_t tiles = ((N + BM - 1) / BM) * ((d + BN - 1) / BN);
+  int s = 1;
+  while (s < 8 && tiles * s < 4096 && (w.ldz / 64) / (s * 2) >= 16) s *= 2;
+  w.dh_splits = s;
+  w.total = w.off_part + (s > 1 ? (size_t)round_up((int64_t)s * N * d * 4, 256) : 0);
   return w;
 }
 
@@ -93,6 +105,8 @@ llamarl_status check_head_shape(int64_t N, int64_t d, int64_t V, llamarl_dtype d
   const int64_t widest = (d > V ? d : V) > N ? (d > V ? d : V) : N;
   if (round_up(widest, 64) * (int64_t)esize(dt) * 256 >= (int64_t)1 << 31)
     return fail(LLAMARL_ERR_UNSUPPORTED, "a 256-row panel of %lld elements per row exceeds 2 GiB", (long long)widest);
+  if (N * d * (int64_t)esize(dt) >= (int64_t)1 << 31)
+    return fail(LLAMARL_ERR_UNSUPPORTED, "H must be smaller than 2 GiB (its rows are gathered with 32-bit offsets)");
   if ((N + BM - 1) / BM * ((V + BN - 1) / BN) >= (int64_t)1 << 31 || V >= (int64_t)1 << 31)
     return fail(LLAMARL_ERR_UNSUPPORTED, "too many tiles");
   return LLAMARL_OK;
@@ -112,14 +126,17 @@ hipError_t set_lds(K kernel, int bytes) {
 
 template <typename TT>
 llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t Nn,
-                                 int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, hipStream_t st) {
+                                 int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, const int32_t* m_count,
+                                 const int32_t* k_count, const int32_t* c_rows, int splits, int64_t split_stride,
+                                 hipStream_t st) {
   StoreArgs a;
+  a.m_count = m_count; a.k_count = k_count; a.c_rows = c_rows; a.splits = splits; a.split_stride = split_stride;
   a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.M = M; a.Nn = Nn; a.K = K;
-  a.tiles_m = (int)((M + BM - 1) / BM);
+  const int tiles_m = (int)((M + BM - 1) / BM);      // worst case: every row active
   a.tiles_n = (int)((Nn + BN - 1) / BN);
   a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
   HIP_TRY(set_lds(k_gemm_store<TT>, MAINLOOP_LDS_BYTES));
-  k_gemm_store<TT><<<dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
+  k_gemm_store<TT><<<dim3((unsigned)(tiles_m * a.tiles_n * splits)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
@@ -134,10 +151,16 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
   a.part_m = reinterpret_cast<float*>(ws + w.off_m);
   a.part_s = reinterpret_cast<float*>(ws + w.off_s);
   a.zt = reinterpret_cast<float*>(ws + w.off_zt);
+  int32_t* rows = reinterpret_cast<int32_t*>(ws + w.off_rows);
+  int32_t* n_act = reinterpret_cast<int32_t*>(ws + w.off_nact);
+  a.rows = rows; a.n_act = n_act;
+  // active-token list (mask and target range); inactive rows get logp = lse = 0 here
+  k_compact_rows<<<dim3(1), dim3(1024), 0, st>>>(0, mask, targets, V, nullptr, N, rows, n_act, logp, lse);
+  HIP_TRY(hipGetLastError());
   HIP_TRY(set_lds(k_fwd_partials<TT>, MAINLOOP_LDS_BYTES));
   k_fwd_partials<TT><<<dim3((unsigned)(w.tiles_v * w.tiles_t)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
   HIP_TRY(hipGetLastError());
-  k_merge_logp<<<dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, targets, mask, N, V,
+  k_merge_logp<<<dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, rows, n_act,
                                                                      w.tiles_v, w.n_pad, logp, lse);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
@@ -153,31 +176,52 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   stt* dzt = reinterpret_cast<stt*>(ws + w.off_dzt);
   stt* wt = reinterpret_cast<stt*>(ws + w.off_wt);
   stt* ht = reinterpret_cast<stt*>(ws + w.off_ht);
+  int32_t* rows = reinterpret_cast<int32_t*>(ws + w.off_rows);
+  int32_t* n_act = reinterpret_cast<int32_t*>(ws + w.off_nact);
 
-  // operand panels for the two gradient contractions: W^T [d][ldz], H^T [d][ldzt] (rows with coef == 0 zeroed)
+  // tokens that carry gradient (coef != 0), and exact zeros for the dH rows of all the others
+  k_compact_rows<<<dim3(1), dim3(1024), 0, st>>>(1, nullptr, nullptr, V, coef, N, rows, n_act, nullptr, nullptr);
+  HIP_TRY(hipGetLastError());
+  k_zero_inactive_rows<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(reinterpret_cast<stt*>(dH), coef, N, d);
+  HIP_TRY(hipGetLastError());
+
+  // operand panels for the two gradient contractions: W^T [d][ldz], and H^T [d][ldzt] of the active tokens only
   k_transpose<stt><<<dim3((unsigned)(w.ldz / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
-      reinterpret_cast<const stt*>(W), V, d, d, wt, w.ldz, nullptr);
+      reinterpret_cast<const stt*>(W), V, d, d, wt, w.ldz, nullptr, nullptr);
   HIP_TRY(hipGetLastError());
   k_transpose<stt><<<dim3((unsigned)(w.ldzt / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
-      reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, coef);
+      reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, rows, n_act);
   HIP_TRY(hipGetLastError());
 
-  // recompute logits tile by tile, turn them into dz in both orientations
+  // recompute logits tile by tile, turn them into dz in both orientations (rows / columns = list positions)
   DzArgs a;
   a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
   a.tiles_v = (int)((V + BM - 1) / BM);
   a.tiles_t = (int)((N + BN - 1) / BN);
-  a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt;
+  a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt; a.rows = rows; a.n_act = n_act;
   const int dz_lds = sizeof(stt) == 2 ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES;
   HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
   k_bwd_dz<TT><<<dim3((unsigned)(a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
   HIP_TRY(hipGetLastError());
 
-  // dH [N,d] = dz [N,V] . W^T[d,V]^T      (K = V, zero-padded to ldz)
-  llamarl_status s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dH, d, dt == LLAMARL_F32, 0, st);
-  if (s != LLAMARL_OK) return s;
-  // dW [V,d] = dz^T [V,N] . H^T[d,N]^T    (K = N, zero-padded to ldzt)
-  return launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW, st);
+  // dH [active rows, d] = dz [n_act,V] . W^T[d,V]^T    (K = V, zero-padded to ldz), scattered to the token rows
+  llamarl_status s;
+  if (w.dh_splits > 1) {
+    float* part = reinterpret_cast<float*>(ws + w.off_part);
+    s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, part, d, 1, 0, n_act, nullptr, nullptr, w.dh_splits,
+                              N * d, st);
+    if (s != LLAMARL_OK) return s;
+    k_reduce_splits<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(part, w.dh_splits, N * d, rows, n_act, d,
+                                                                 reinterpret_cast<stt*>(dH), d);
+    HIP_TRY(hipGetLastError());
+  } else {
+    s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dH, d, dt == LLAMARL_F32, 0, n_act, nullptr, rows, 1,
+                              0, st);
+    if (s != LLAMARL_OK) return s;
+  }
+  // dW [V,d] = dz^T [V,n_act] . H^T[d,n_act]^T          (K = n_act, zero-padded to a multiple of 64)
+  return launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW,
+                               nullptr, n_act, nullptr, 1, 0, st);
 }
 
 }  // namespace
