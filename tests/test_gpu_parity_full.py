@@ -1,0 +1,159 @@
+"""GPU parity at the full sizes of the five named workloads, in the launch configuration bench.py times.
+
+The oracle cannot form [N,V] logits in fp64 for these shapes, so it is asked for what it can compute one by one:
+  * log-probs / lse / coef / dH for a sample of token rows (each needs only its own logits row),
+  * the WHOLE dW of a backward pass whose gradient weight is restricted to a sample of rows (dW is linear in
+    coef, so this pins every dW element against the oracle at the full V x d shape),
+and the rest is checked through properties that hold at any size: masked rows exactly zero, loss equal to the
+fp64 sum of coef * logp, vocabulary column sums of dW vanishing, N_valid exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import aipo_oracle as orc
+from paper_2505_24034_amd import synth
+from parity_util import check_grad, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(x, n, rng):
+    """Valid rows: first / last valid token of every generation, rows next to 256-row tile edges, random ones."""
+    mask = x["mask"].cpu().numpy()
+    B, T = mask.shape
+    valid = np.nonzero(mask.reshape(-1))[0]
+    picks = []
+    for b in range(B):
+        ln = int(mask[b].sum())
+        if ln:
+            picks += [b * T, b * T + ln - 1]
+    vs = set(valid.tolist())
+    for e in (255, 256, 257, 511, 512):
+        picks += [r for r in (e, valid[-1] - e) if r in vs]
+    extra = rng.choice(valid, size=max(0, n - len(set(picks))), replace=False)
+    return np.array(sorted(set(picks) | set(extra.tolist())))[: max(n, len(set(picks)))]
+
+
+@pytest.mark.parametrize("name,n_rows,n_dw_rows", [
+    ("llama3_8b", 128, 256),
+    ("llama3_70b", 96, 128),
+    ("long_reasoning", 128, 256),
+    ("llama3_405b_head", 64, 96),
+])
+def test_full_size_workload(lib, name, n_rows, n_dw_rows):
+    w = synth.WORKLOADS[name]
+    print("workload", name, "d", w.d, "V", w.V, "B", w.B, "T", w.T, flush=True)
+    x = synth.make_inputs(w, "cuda")
+    B, T, N, V = w.B, w.T, w.N, w.V
+    mask_flat = x["mask"].reshape(-1)
+    rho = 2.0
+    logp, lse = lib.token_logprobs(x["H"], x["W"], x["targets"], mask_flat)
+    loss, coef, stats = lib.offpolicy_loss_fwd(logp, x["mu_logp"], x["adv"], x["mask"], B, T, rho=rho,
+                                               targets=x["targets"], V=V)
+    dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef)
+    torch.cuda.synchronize()
+
+    # ---- properties that hold at any size
+    dead = mask_flat == 0
+    n_valid = int((~dead).sum())
+    assert float(stats[0]) == n_valid and float(stats[4]) == 0
+    assert not bool(logp[dead].any()) and not bool(lse[dead].any()) and not bool(coef[dead].any())
+    assert not bool(dH[dead].any())
+    assert bool(torch.isfinite(dW).all()) and bool(torch.isfinite(dH).all())
+    terms = coef.double() * logp.double()
+    assert abs(float(loss) - float(terms.sum())) <= 1e-5 * float(terms.abs().sum()) + 1e-7
+    colsum = dW.double().sum(dim=0)
+    assert float(colsum.abs().max()) <= 1e-2 * float(dW.double().abs().sum(dim=0).max())
+
+    # ---- sampled rows against the oracle
+    rng = np.random.default_rng(w.seed)
+    rows = _sample_rows(x, n_rows, rng)
+    ridx = torch.as_tensor(rows, device="cuda")
+    Hs, Ws = synth.to_oracle(x["H"][ridx]), synth.to_oracle(x["W"])
+    tg = synth.to_oracle(x["targets"][ridx])
+    o_logp, o_lse = orc.token_logprobs(Hs, Ws, tg)
+    assert np.abs(f64(logp[ridx]) - o_logp).max() <= 2e-2
+    assert np.abs(f64(lse[ridx]) - o_lse).max() <= 2e-2
+    # oracle coef for the sampled rows: ratio, clip and advantage per token, normaliser from the whole mask
+    full_logp = np.zeros(N)
+    full_logp[rows] = o_logp
+    o = orc.offpolicy_loss_fwd(full_logp, synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]),
+                               synth.to_oracle(x["mask"]), rho)
+    o_coef = o["coef"][rows]
+    assert np.abs(f64(coef[ridx]) - o_coef).max() <= 2.5e-2 * np.abs(o_coef).max()
+    o_dH, _ = orc.offpolicy_loss_bwd(Hs, Ws, tg, o_lse, o_coef)
+    check_grad("dH[sampled rows]", f64(dH[ridx]), o_dH, "bf16")
+
+    # ---- the whole dW of a pass whose gradient weight lives on a sample of rows
+    if n_dw_rows:
+        drows = _sample_rows(x, n_dw_rows, rng)
+        didx = torch.as_tensor(drows, device="cuda")
+        coef_s = torch.zeros_like(coef)
+        coef_s[didx] = coef[didx]
+        dH_s, dW_s = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef_s, dW_dtype=torch.float32)
+        torch.cuda.synchronize()
+        Hd = synth.to_oracle(x["H"][didx])
+        _, o_dW = orc.offpolicy_loss_bwd(Hd, Ws, synth.to_oracle(x["targets"][didx]), f64(lse[didx]),
+                                         f64(coef[didx]))
+        ref = torch.as_tensor(o_dW, device="cuda")
+        err = (dW_s.double() - ref)
+        fro = float(err.norm() / ref.norm())
+        mx = float(err.abs().max() / ref.abs().max())
+        assert fro <= 1e-2 and mx <= 1e-2, (fro, mx)
+        keep = torch.zeros(N, dtype=torch.bool, device="cuda")
+        keep[didx] = True
+        assert not bool(dH_s[~keep].any())
+
+
+def test_config2_every_output_against_the_oracle(lib):
+    """Llama-3-8B shape, exhaustive: the fp64 oracle is run over all valid rows in row chunks (rows are
+    independent; dW is the sum of the chunks' dW), so every logp, lse, coef, dH and dW element is compared."""
+    w = synth.WORKLOADS["llama3_8b"]
+    x = synth.make_inputs(w, "cuda")
+    B, T, N, V = w.B, w.T, w.N, w.V
+    rho = 2.0
+    mask_flat = x["mask"].reshape(-1)
+    logp, lse = lib.token_logprobs(x["H"], x["W"], x["targets"], mask_flat)
+    loss, coef, stats = lib.offpolicy_loss_fwd(logp, x["mu_logp"], x["adv"], x["mask"], B, T, rho=rho,
+                                               targets=x["targets"], V=V)
+    dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef, dW_dtype=torch.float32)
+    torch.cuda.synchronize()
+
+    Wd = orc.widen(synth.to_oracle(x["W"]))
+    valid = np.nonzero(synth.to_oracle(mask_flat))[0]
+    o_logp, o_lse = np.zeros(N), np.zeros(N)
+    chunk = 1024
+    for c0 in range(0, valid.size, chunk):
+        r = valid[c0:c0 + chunk]
+        ridx = torch.as_tensor(r, device="cuda")
+        lp, ls = orc.token_logprobs(synth.to_oracle(x["H"][ridx]), Wd, synth.to_oracle(x["targets"][ridx]))
+        o_logp[r], o_lse[r] = lp, ls
+        print("oracle forward rows", c0 + r.size, "/", valid.size, flush=True)
+    assert np.abs(f64(logp) - o_logp).max() <= 2e-2 and np.abs(f64(lse) - o_lse).max() <= 2e-2
+    o = orc.offpolicy_loss_fwd(o_logp, synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]),
+                               synth.to_oracle(x["mask"]), rho, targets=synth.to_oracle(x["targets"]), V=V)
+    assert np.array_equal(f64(coef) == 0, o["coef"] == 0)
+    assert np.abs(f64(coef) - o["coef"]).max() <= 2.5e-2 * np.abs(o["coef"]).max()
+    assert abs(float(loss) - o["loss"]) <= 1e-2 * np.abs(o["coef"] * o_logp).sum()
+    assert float(stats[0]) == o["stats"][0]
+    assert np.allclose(f64(stats)[1:4], o["stats"][1:4], rtol=0, atol=2.5e-2)
+
+    o_dW = np.zeros((V, w.d))
+    dH_err2 = dH_ref2 = 0.0
+    dH_max_err = dH_max_ref = 0.0
+    for c0 in range(0, valid.size, chunk):
+        r = valid[c0:c0 + chunk]
+        ridx = torch.as_tensor(r, device="cuda")
+        gH, gW = orc.offpolicy_loss_bwd(synth.to_oracle(x["H"][ridx]), Wd, synth.to_oracle(x["targets"][ridx]),
+                                        o_lse[r], o["coef"][r])
+        o_dW += gW
+        e = f64(dH[ridx]) - gH
+        dH_err2 += float((e * e).sum()); dH_ref2 += float((gH * gH).sum())
+        dH_max_err = max(dH_max_err, float(np.abs(e).max())); dH_max_ref = max(dH_max_ref, float(np.abs(gH).max()))
+        print("oracle backward rows", c0 + r.size, "/", valid.size, flush=True)
+    assert (dH_err2 / dH_ref2) ** 0.5 <= 1e-2 and dH_max_err <= 1e-2 * dH_max_ref
+    assert not bool(dH[mask_flat == 0].any())
+    ref = torch.as_tensor(o_dW, device="cuda")
+    err = dW.double() - ref
+    assert float(err.norm() / ref.norm()) <= 1e-2 and float(err.abs().max() / ref.abs().max()) <= 1e-2
