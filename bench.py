@@ -30,10 +30,13 @@ def cpu_baseline(x, w, rows):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    H = synth.to_oracle(x["H"][:rows])
+    import torch
+    idx = torch.nonzero(x["mask"].reshape(-1))[:rows, 0]
+    rows = int(idx.numel())
+    H = synth.to_oracle(x["H"][idx])
     W = synth.to_oracle(x["W"])
-    tg = synth.to_oracle(x["targets"][:rows])
-    mu = synth.to_oracle(x["mu_logp"][:rows])
+    tg = synth.to_oracle(x["targets"][idx])
+    mu = synth.to_oracle(x["mu_logp"][idx])
     adv = np.array([1.0])
     mask = np.ones((1, rows), dtype=np.uint8)
     t0 = time.perf_counter()
@@ -41,8 +44,22 @@ def cpu_baseline(x, w, rows):
     dt = time.perf_counter() - t0
     assert np.isfinite(out["loss"])
     return {"value": rows / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "first %d valid rows of the batch (one generation prefix), full V=%d and d=%d, fwd+bwd once, "
+            "sample": "first %d valid token rows of the batch, full V=%d and d=%d, oracle fwd+bwd once, "
                       "%.1f s; cost is linear in rows" % (rows, w.V, w.d, dt)}
+
+
+def measured_traffic(kernel):
+    """Bytes per launch of `kernel` between L2 and the fabric (reads include Infinity-Cache hits), from the committed
+    rocprofv3 FETCH_SIZE / WRITE_SIZE summary, already scaled by the plain-copy calibration.  None if absent."""
+    path = os.path.join(ROOT, "profiles", "bench_llama3_8b_hbm_traffic_pmc.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) >= 6 and kernel in cells[1]:
+                return (float(cells[4]) + float(cells[5])) * 2 ** 30
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def main():
@@ -51,8 +68,19 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b")
-    ap.add_argument("--cpu-rows", type=int, default=512, help="rows of the bounded oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the bounded oracle sample (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run three plain 1 GiB device copies and exit (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": 1 << 30, "copies": 3}))
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
@@ -127,7 +155,11 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "k_fwd_partials<BF16> (LM-head contraction + online logsumexp), "
                      "timed as llamarl_token_logprobs; 2*n_valid*V*d flop per launch",
                      "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": fwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": fwd_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": measured_traffic("k_fwd_partials") if w.name == "llama3_8b" else None,
+                     "traffic_note": "bytes per launch, rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0 (plain-copy "
+                                     "calibration); algorithmic bytes are W + active H rows = %.3g" %
+                                     ((V * d + n_valid * d) * (2 if w.dtype == "bf16" else 4))},
     }
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(x, w, args.cpu_rows)
