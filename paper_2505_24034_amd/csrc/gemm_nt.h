@@ -18,6 +18,8 @@
 //     ds_read_b128 is issued in the shadow of an MFMA one k-substep ahead of its use, and scheduling fences
 //     pin that interleave (the compiler's own schedule exposes the LDS latency).
 //   - out-of-range rows and the K tail use the buffer descriptor's bounds check: such lanes read zeros.
+//   - kernels are persistent (one workgroup per CU walks a list of tiles) and fetch the first slabs of their next
+//     tile before the epilogue of the current one, so the epilogue's VALU work overlaps that latency.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -86,51 +88,80 @@ struct LanePos {
   __device__ __forceinline__ int col(int j) const { return wn * WAVE_N + j * 32 + (lane & 31); }
 };
 
-// blockIdx -> (tile_m, tile_n), or false if this block has no tile.  The grid is sized on the host for the
-// worst case; tiles_m x tiles_n is the number of tiles that exist once the device-side active-row count is known.
-// Workgroups are dealt round-robin to the 8 XCDs, each with a private L2: every XCD gets a contiguous, equally
-// long run of tile ids, and ids are ordered so that 32 consecutive ones form an 8 x 4 patch sharing A and B panels.
-__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
-  const int nact = tiles_m * tiles_n;
-  const int bid = blockIdx.x;
-  const int xcd = bid & 7, local = bid >> 3;
-  const int base = nact >> 3, rem = nact & 7;
-  if (local >= base + (xcd < rem ? 1 : 0)) return false;
-  const int id = xcd * base + min(xcd, rem) + local;
-  constexpr int GROUP_M = 8;
-  const int per_group = GROUP_M * tiles_n;
-  const int g = id / per_group;
-  const int first_m = g * GROUP_M;
-  const int gsize = min(tiles_m - first_m, GROUP_M);
-  const int in_g = id - g * per_group;
-  tm = first_m + in_g % gsize;
-  tn = in_g / gsize;
-  return true;
-}
+// Persistent tile schedule.  The grid has one workgroup per CU (any size works); workgroups are dealt round-robin
+// to the 8 XCDs, each with a private L2.  Every XCD owns a contiguous run of tile ids and its workgroups walk it
+// in lock-step, so the tiles an XCD works on at any time are consecutive ids; ids are ordered so that 32
+// consecutive ones form an 8 x 4 patch that shares A and B panels.  tiles_m x tiles_n is the number of tiles that
+// exist once the device-side active-row count is known.
+struct TileSchedule {
+  int tiles_m, tiles_n;
+  int next_id, end_id, stride;
+  __device__ __forceinline__ void init(int tiles_m_, int tiles_n_) {
+    tiles_m = tiles_m_;
+    tiles_n = tiles_n_;
+    const int ntiles = tiles_m * tiles_n;
+    const int bid = blockIdx.x, nblk = gridDim.x;
+    const int xcd = bid & 7, local = bid >> 3;
+    const int base = ntiles >> 3, rem = ntiles & 7;
+    const int start = xcd * base + min(xcd, rem);
+    end_id = start + base + (xcd < rem ? 1 : 0);
+    next_id = start + local;
+    stride = (nblk >> 3) + ((nblk & 7) > xcd ? 1 : 0);      // workgroups of this grid that sit on my XCD
+  }
+  __device__ __forceinline__ bool has_tile() const { return next_id < end_id; }
+  __device__ __forceinline__ int take() {                   // id of the next tile; advance
+    const int id = next_id;
+    next_id += stride;
+    return id;
+  }
+  __device__ __forceinline__ void coords(int id, int& tm, int& tn) const {
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int g = id / per_group;
+    const int first_m = g * GROUP_M;
+    const int gsize = min(tiles_m - first_m, GROUP_M);
+    const int in_g = id - g * per_group;
+    tm = first_m + in_g % gsize;
+    tn = in_g / gsize;
+  }
+};
 
 __device__ __forceinline__ int swizzle(int row) { return (row >> 1) & 7; }
 
-// One operand slab stream: 256 rows x 128 bytes per step, this thread's four 16-byte chunks.
+// One operand slab stream: 256 rows x 128 bytes per step; this thread moves four 16-byte chunks of it.
+// Wave-instruction `it` of wave w fills rows (it*8 + w)*8 .. +7 of the slab; lane l takes row +l/8 and the
+// physical 16-byte slot l%8.  Because it*64 rows is a multiple of 16, the swizzle (and so the logical chunk this
+// lane fetches) is the same for all four instructions.
 template <typename TT>
 struct SlabLoader {
-  __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t voff[4];       // per-lane byte offset of (row, logical chunk) inside the tile, k = 0
-  uint32_t chunk_k[4];    // first k (elements) of that logical chunk inside a slab
-  int lds_row0[4];        // first row of the 8-row group this wave-instruction fills
+  // The buffer descriptor is rebuilt from these at every use; readfirstlane pins them to scalar registers, so
+  // the compiler never has to guess that the descriptor is wave-uniform (a guess it loses across loops).
+  uint32_t base_lo, base_hi, records;
+  uint32_t voff[4];       // per-lane byte offset of (row, logical chunk) inside the panel at k = 0
 
+  __device__ __forceinline__ void set_base(const void* base, uint32_t bytes) {
+    const uint64_t p = reinterpret_cast<uint64_t>(base);
+    base_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    base_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+    records = (uint32_t)__builtin_amdgcn_readfirstlane((int)bytes);
+  }
+  __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc() const {
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)base_hi << 32) | base_lo), 0,
+                                             (int)records, 0x00020000);
+  }
+
+  __device__ __forceinline__ static int lane_chunk(int wave, int lane) {
+    return (lane & 7) ^ swizzle(wave * 8 + (lane >> 3));
+  }
   // base: first row of the tile; ld in elements; rows_valid <= 256 rows exist from base on.
   __device__ __forceinline__ void init(const void* base, int64_t ld, int rows_valid, int wave, int lane) {
     const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
-    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(row_bytes * (uint32_t)rows_valid),
-                                             0x00020000);
+    set_base(base, row_bytes * (uint32_t)rows_valid);
+    const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int r0 = (it * 8 + wave) * 8;
-      const int row = r0 + (lane >> 3);
-      const int c = (lane & 7) ^ swizzle(row);
-      lds_row0[it] = r0;
-      chunk_k[it] = (uint32_t)(c * TT::EPC);
-      voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + (uint32_t)c * 16u : OOB_OFFSET;
+      const int row = (it * 8 + wave) * 8 + (lane >> 3);
+      voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + c16 : OOB_OFFSET;
     }
   }
   // Gathered panel: tile row r is row rows[r] of the whole matrix `base` (total_rows rows, < 2^31 bytes).
@@ -138,31 +169,30 @@ struct SlabLoader {
   __device__ __forceinline__ void init_gather(const void* base, int64_t ld, int64_t total_rows, const int32_t* rows,
                                               int rows_valid, int wave, int lane) {
     const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
-    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)((uint32_t)total_rows * row_bytes),
-                                             0x00020000);
+    set_base(base, (uint32_t)total_rows * row_bytes);
+    const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int r0 = (it * 8 + wave) * 8;
-      const int row = r0 + (lane >> 3);
-      const int c = (lane & 7) ^ swizzle(row);
-      lds_row0[it] = r0;
-      chunk_k[it] = (uint32_t)(c * TT::EPC);
-      voff[it] = (row < rows_valid) ? (uint32_t)rows[row] * row_bytes + (uint32_t)c * 16u : OOB_OFFSET;
+      const int row = (it * 8 + wave) * 8 + (lane >> 3);
+      voff[it] = (row < rows_valid) ? (uint32_t)rows[row] * row_bytes + c16 : OOB_OFFSET;
     }
   }
   // k0: first k of the slab (elements); K: contraction length.  lds: start of this operand's slab in LDS.
-  __device__ __forceinline__ void issue(char* lds, int64_t k0, int64_t K) const {
-    const int soff = (int)(k0 * (int64_t)sizeof(typename TT::store_t));
-    const bool tail = k0 + 8 * TT::EPC > K;
+  __device__ __forceinline__ void issue(char* lds, int k0, int K, int wave, int lane) const {
+    const int soff = k0 * (int)sizeof(typename TT::store_t);
+    // K tail: this lane's chunk lies past K (only in the last slab)
+    const bool cut = k0 + lane_chunk(wave, lane) * TT::EPC >= K;
+    const __amdgpu_buffer_rsrc_t r = rsrc();
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      uint32_t v = voff[it];
-      if (tail && k0 + chunk_k[it] >= K) v = OOB_OFFSET;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(lds + lds_row0[it] * SLAB_ROW_BYTES), 16, (int)v,
-                                               soff, 0, 0);
+      const uint32_t v = cut ? OOB_OFFSET : voff[it];
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(lds + (it * 8 + wave) * 8 * SLAB_ROW_BYTES), 16,
+                                               (int)v, soff, 0, 0);
     }
   }
 };
+
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 #define LLAMARL_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -199,9 +229,12 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
   }
 }
 
-// The main loop.  A_tile/B_tile point at the first row of this tile's operand panels.
-// smem must hold MAINLOOP_LDS_BYTES.  Waves leave the loop at different times: a caller that reuses smem
-// must __syncthreads() first.
+// The main loop, split in two so that a persistent workgroup can start fetching its NEXT tile before it runs the
+// epilogue of the current one:
+//   prefetch(): set up both operand streams of a tile and issue its first two K slabs.  Only legal once every
+//               wave of the workgroup is done reading LDS (a __syncthreads() after the previous run()).
+//   run():      the K loop.  Waves leave it at different times: __syncthreads() before reusing LDS.
+// smem must hold MAINLOOP_LDS_BYTES.
 //
 // Per slab kt (4 k-substeps s = 0..3, fragment sets f0/f1 alternate):
 //   s=0..2 : MFMAs of substep s, reads of substep s+1 from slab kt
@@ -209,83 +242,89 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
 //   issue  : slab kt+2 -> the buffer slab kt just vacated
 //   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1
 //
-// b_rows != nullptr: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
+// GATHER_B: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
 // tile row r is its row b_rows[r].
 template <typename TT>
-__device__ __forceinline__ void gemm_nt_mainloop(const void* A_tile, int64_t lda, int rowsA, const void* B_tile,
-                                                 int64_t ldb, int rowsB, int64_t K, char* smem,
-                                                 f32x16_t (&acc)[TM][TN], const int32_t* b_rows = nullptr,
-                                                 int64_t b_total = 0) {
+struct TileGemm {
   typedef typename TT::frag_t frag_t;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  constexpr int BK = 8 * TT::EPC;
-
+  static constexpr int BK = 8 * TT::EPC;
   SlabLoader<TT> la, lb;
-  la.init(A_tile, lda, rowsA, wave, lane);
-  if (b_rows != nullptr) lb.init_gather(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
-  else lb.init(B_tile, ldb, rowsB, wave, lane);
+  int K;
 
+  template <bool GATHER_B>
+  __device__ __forceinline__ void prefetch(const void* A_tile, int64_t lda, int rowsA, const void* B_tile, int64_t ldb,
+                                           int rowsB, int64_t K_, char* smem, const int32_t* b_rows = nullptr,
+                                           int64_t b_total = 0) {
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    K = (int)K_;
+    la.init(A_tile, lda, rowsA, wave, lane);
+    if constexpr (GATHER_B) lb.init_gather(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
+    else lb.init(B_tile, ldb, rowsB, wave, lane);
+    la.issue(smem, 0, K, wave, lane);
+    lb.issue(smem + SLAB_A_BYTES, 0, K, wave, lane);
+    if (K > BK) {
+      la.issue(smem + STAGE_BYTES, BK, K, wave, lane);
+      lb.issue(smem + STAGE_BYTES + SLAB_A_BYTES, BK, K, wave, lane);
+    }
+  }
+
+  __device__ __forceinline__ void run(char* smem, f32x16_t (&acc)[TM][TN]) {
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = (K + BK - 1) / BK;
+    // per-lane read addresses: row = lane % 32 inside a 32-row block, chunk pair (2s, 2s+1) split over half-waves
+    const int half = lane >> 5;
+    const int arow = wm * WAVE_M + (lane & 31), brow = wn * WAVE_N + (lane & 31);
+    int a_addr[4], b_addr[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      a_addr[s] = arow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(arow)) * 16);
+      b_addr[s] = SLAB_A_BYTES + brow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(brow)) * 16);
+    }
+    // Slabs 0 and 1 were issued by prefetch(); stores of a previous epilogue may sit between them and now in the
+    // vmcnt queue, so wait for everything rather than count.
+    wait_vmcnt0();
+    __syncthreads();
+    Frags<TT> f0, f1;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      f0.a[i] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + i * 32 * SLAB_ROW_BYTES);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      f0.b[j] = *reinterpret_cast<const frag_t*>(smem + b_addr[0] + j * 32 * SLAB_ROW_BYTES);
 
-  const int nk = (int)((K + BK - 1) / BK);
-  // per-lane read addresses: row = lane % 32 inside a 32-row block, chunk pair (2s, 2s+1) split over half-waves
-  const int half = lane >> 5;
-  const int arow = wm * WAVE_M + (lane & 31), brow = wn * WAVE_N + (lane & 31);
-  int a_addr[4], b_addr[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    a_addr[s] = arow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(arow)) * 16);
-    b_addr[s] = SLAB_A_BYTES + brow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(brow)) * 16);
-  }
-
-  char* buf0 = smem;
-  char* buf1 = smem + STAGE_BYTES;
-  la.issue(buf0, 0, K);
-  lb.issue(buf0 + SLAB_A_BYTES, 0, K);
-  if (nk > 1) {
-    la.issue(buf1, BK, K);
-    lb.issue(buf1 + SLAB_A_BYTES, BK, K);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | 8);   // vmcnt(8): slab 0 landed, the 8 loads of slab 1 may be in flight
-  } else {
-    wait_vmcnt0();
-  }
-  __syncthreads();
-  Frags<TT> f0, f1;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) f0.a[i] = *reinterpret_cast<const frag_t*>(buf0 + a_addr[0] + i * 32 * SLAB_ROW_BYTES);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) f0.b[j] = *reinterpret_cast<const frag_t*>(buf0 + b_addr[0] + j * 32 * SLAB_ROW_BYTES);
-
-  for (int kt = 0; kt < nk - 1; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE_BYTES;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-    LLAMARL_FENCE();
-    k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
-    k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
-    k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
-    wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
-    __syncthreads();    // everyone's has, and everyone is done reading slab kt
-    if (kt + 2 < nk) {
-      la.issue(cur, (int64_t)(kt + 2) * BK, K);
-      lb.issue(cur + SLAB_A_BYTES, (int64_t)(kt + 2) * BK, K);
+    for (int kt = 0; kt < nk - 1; ++kt) {
+      char* cur = smem + (kt & 1) * STAGE_BYTES;
+      char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+      LLAMARL_FENCE();
+      k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
+      k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
+      k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
+      wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
+      __syncthreads();    // everyone's has, and everyone is done reading slab kt
+      if (kt + 2 < nk) {
+        la.issue(cur, (kt + 2) * BK, K, wave, lane);
+        lb.issue(cur + SLAB_A_BYTES, (kt + 2) * BK, K, wave, lane);
+      }
+      LLAMARL_FENCE();
+      k_substep<TT>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true);
     }
-    LLAMARL_FENCE();
-    k_substep<TT>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true);
+    {
+      const char* cur = smem + ((nk - 1) & 1) * STAGE_BYTES;
+      LLAMARL_FENCE();
+      k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
+      k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
+      k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
+      k_substep<TT>(f1, f0, cur, 0, 0, acc, false);
+    }
   }
-  {
-    const char* cur = smem + ((nk - 1) & 1) * STAGE_BYTES;
-    LLAMARL_FENCE();
-    k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
-    k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
-    k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
-    k_substep<TT>(f1, f0, cur, 0, 0, acc, false);
-  }
-}
+};
 
 }  // namespace llamarl

@@ -44,72 +44,104 @@ struct FwdArgs {
   const int32_t* n_act;   // device scalar
 };  // partials and zt are indexed by compacted position, not by token
 
+// both operand streams of tile `id` of the logits kernels (rows = W tile, columns = gathered H rows), first two slabs
+template <typename TT, typename Args>
+__device__ __forceinline__ void fwd_fetch(TileGemm<TT>& g, const TileSchedule& sch, const Args& a, int id, int n_act,
+                                          char* smem) {
+  typedef typename TT::store_t st;
+  int tv, tt;
+  sch.coords(id, tv, tt);
+  g.template prefetch<true>((const st*)a.W + (int64_t)tv * BM * a.d, a.d, (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
+             (int)min((int64_t)BN, (int64_t)n_act - (int64_t)tt * BN), a.d, smem, a.rows + (int64_t)tt * BN, a.N);
+}
+
+constexpr int FWD_LDS_BYTES = MAINLOOP_LDS_BYTES + 2 * 2 * BN * 4;   // + per-token (max, sum) of the two wave rows
+
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int tv, tt;
-  const int n_act = *a.n_act;
-  if (!tile_coords(a.tiles_v, (n_act + BN - 1) / BN, tv, tt)) return;   // block-uniform: token tiles of masked rows
-  const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
-  const int rowsV = (int)min((int64_t)BM, a.V - v0);
-  const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
   typedef typename TT::store_t st;
-  f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, a.H, a.d, rowsT, a.d, smem, acc, a.rows + t0, a.N);
-
+  const int n_act = *a.n_act;
+  TileSchedule sch;
+  sch.init(a.tiles_v, (n_act + BN - 1) / BN);        // token tiles that hold active rows only
+  if (!sch.has_tile()) return;                       // block-uniform
   const int tid = threadIdx.x;
-  LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
-  __syncthreads();
-  float* s_m = reinterpret_cast<float*>(smem);     // [2 waves along the vocabulary][256 tokens]
-  float* s_s = s_m + 2 * BN;
+  const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  float* s_m = reinterpret_cast<float*>(smem + MAINLOOP_LDS_BYTES);   // [2 waves along the vocabulary][256 tokens]
+  float* s_s = s_m + 2 * BN;                                          // outside the slab buffers: see prefetch below
 
-  if (rowsV < BM) {   // last vocab tile only (block-uniform): rows past V must not enter the softmax
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (lp.row(i, r) >= rowsV) acc[i][j][r] = -INFINITY;
-  }
-  const int lane_row0 = lp.row(0, 0);                // rows of this lane: lane_row0 + i*32 + (r/4)*8 + r%4
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int tok = lp.col(j);
-    const int y = (tok < rowsT) ? a.targets[a.rows[t0 + tok]] : -1;
-    const int yrow = y - (int)v0;                    // vocab row of the target inside this tile (if 0 <= . < rowsV)
-    const int yrel = yrow - lane_row0;               // ... relative to this lane's first row
-    float m = -INFINITY, zy = 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        m = fmaxf(m, acc[i][j][r]);
-        zy = (yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? acc[i][j][r] : zy;
-      }
-    m = fmaxf(m, __shfl_xor(m, 32));
-    const float mb = (m == -INFINITY) ? 0.f : m * LOG2E;
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[i][j][r], LOG2E, -mb));   // exp2(-inf) = 0
-    s += __shfl_xor(s, 32);
-    const bool mine = yrel >= 0 && yrel < WAVE_M && (yrel & 4) == 0;                   // one of this lane's rows
-    if (mine && y >= 0 && yrow < rowsV && tok < rowsT) a.zt[t0 + tok] = zy;
-    if ((lp.lane >> 5) == 0) {
-      s_m[lp.wm * BN + tok] = m;
-      s_s[lp.wm * BN + tok] = s;
+  TileGemm<TT> g;
+  int id = sch.take();
+  fwd_fetch<TT>(g, sch, a, id, n_act, smem);
+  while (true) {
+    f32x16_t acc[TM][TN];
+    g.run(smem, acc);
+    int tv, tt;
+    sch.coords(id, tv, tt);
+    const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
+    const int rowsV = (int)min((int64_t)BM, a.V - v0);
+    const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
+    const bool more = sch.has_tile();
+    __syncthreads();                                 // every wave is done reading the slab buffers
+    if (more) {                                      // start the next tile's first slabs; the epilogue hides them
+      id = sch.take();
+      fwd_fetch<TT>(g, sch, a, id, n_act, smem);
     }
-  }
-  __syncthreads();
-  if (tid < rowsT) {
-    const float m0 = s_m[tid], m1 = s_m[BN + tid];
-    const float M = fmaxf(m0, m1);
-    const float Mb = (M == -INFINITY) ? 0.f : M;
-    const float S = s_s[tid] * __expf(m0 - Mb) + s_s[BN + tid] * __expf(m1 - Mb);
-    a.part_m[(int64_t)tv * a.n_pad + t0 + tid] = M;
-    a.part_s[(int64_t)tv * a.n_pad + t0 + tid] = S;
+
+    if (rowsV < BM) {   // last vocab tile only (block-uniform): rows past V must not enter the softmax
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (lp.row(i, r) >= rowsV) acc[i][j][r] = -INFINITY;
+    }
+    const int lane_row0 = lp.row(0, 0);              // rows of this lane: lane_row0 + i*32 + (r/4)*8 + r%4
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int tok = lp.col(j);
+      const int y = (tok < rowsT) ? a.targets[a.rows[t0 + tok]] : -1;
+      const int yrow = y - (int)v0;                  // vocab row of the target inside this tile (if 0 <= . < rowsV)
+      const int yrel = yrow - lane_row0;             // ... relative to this lane's first row
+      float m = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[i][j][r]);
+      m = fmaxf(m, __shfl_xor(m, 32));
+      const float mb = (m == -INFINITY) ? 0.f : m * LOG2E;
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[i][j][r], LOG2E, -mb));   // exp2(-inf) = 0
+      s += __shfl_xor(s, 32);
+      // target logit: one lane of one wave of one vocab tile owns row y_t of a token; most waves own none
+      const bool mine = y >= 0 && yrow < rowsV && tok < rowsT && yrel >= 0 && yrel < WAVE_M && (yrel & 4) == 0;
+      if (__any(mine)) {                             // wave-uniform
+        float zy = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) zy = (yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? acc[i][j][r] : zy;
+        if (mine) a.zt[t0 + tok] = zy;
+      }
+      if ((lp.lane >> 5) == 0) {
+        s_m[lp.wm * BN + tok] = m;
+        s_s[lp.wm * BN + tok] = s;
+      }
+    }
+    __syncthreads();
+    if (tid < rowsT) {
+      const float m0 = s_m[tid], m1 = s_m[BN + tid];
+      const float M = fmaxf(m0, m1);
+      const float Mb = (M == -INFINITY) ? 0.f : M;
+      const float S = s_s[tid] * __expf(m0 - Mb) + s_s[BN + tid] * __expf(m1 - Mb);
+      a.part_m[(int64_t)tv * a.n_pad + t0 + tid] = M;
+      a.part_s[(int64_t)tv * a.n_pad + t0 + tid] = S;
+    }
+    if (!more) break;
   }
 }
 
@@ -226,119 +258,135 @@ struct DzArgs {
 template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int tv, tt;
-  const int n_act = *a.n_act;
-  if (!tile_coords(a.tiles_v, (n_act + BN - 1) / BN, tv, tt)) return;   // block-uniform: no active token there
-  const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
-  const int rowsV = (int)min((int64_t)BM, a.V - v0);
-  const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
   typedef typename TT::store_t st;
-  f32x16_t acc[TM][TN];
-  gemm_nt_mainloop<TT>((const st*)a.W + v0 * a.d, a.d, rowsV, a.H, a.d, rowsT, a.d, smem, acc, a.rows + t0, a.N);
-
+  const int n_act = *a.n_act;
+  TileSchedule sch;
+  sch.init(a.tiles_v, (n_act + BN - 1) / BN);
+  if (!sch.has_tile()) return;                       // block-uniform: no active token at all
   const int tid = threadIdx.x;
-  LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  TileGemm<TT> g;
+  while (sch.has_tile()) {
+    int tv, tt;
+    sch.coords(sch.take(), tv, tt);
+    const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
+    const int rowsV = (int)min((int64_t)BM, a.V - v0);
+    const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
+    // the bf16 epilogue stages the whole tile through LDS, so the next tile cannot be fetched under it
+    g.template prefetch<true>((const st*)a.W + v0 * a.d, a.d, rowsV, a.H, a.d, rowsT, a.d, smem, a.rows + t0, a.N);
+    f32x16_t acc[TM][TN];
+    g.run(smem, acc);
 
-  // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
-  const int lane_row0 = lp.row(0, 0);
+    // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
+    const int lane_row0 = lp.row(0, 0);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int tok = lp.col(j);
-    const bool in = tok < rowsT;
-    const int64_t t = in ? a.rows[t0 + tok] : 0;
-    const float c = in ? a.g * a.coef[t] : 0.f;
-    const float lb = (c != 0.f) ? a.lse[t] * LOG2E : 0.f;
-    const int yrel = (in ? a.targets[t] : -1) - (int)v0 - lane_row0;
-    const bool live = c != 0.f;                              // select: a masked token's row is exactly 0
+    for (int j = 0; j < TN; ++j) {
+      const int tok = lp.col(j);
+      const bool in = tok < rowsT;
+      const int64_t t = in ? a.rows[t0 + tok] : 0;
+      const float c = in ? a.g * a.coef[t] : 0.f;
+      const float lb = (c != 0.f) ? a.lse[t] * LOG2E : 0.f;
+      const int yrel = (in ? a.targets[t] : -1) - (int)v0 - lane_row0;
+      const bool live = c != 0.f;                            // select: a masked token's row is exactly 0
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = fast_exp2(fmaf(acc[i][j][r], LOG2E, -lb));
-        const float onehot = (yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? 1.f : 0.f;
-        acc[i][j][r] = live ? c * (onehot - p) : 0.f;
-      }
-  }
-  if (rowsV < BM) {   // last vocab tile only (block-uniform): padded vocab rows are 0
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (lp.row(i, r) >= rowsV) acc[i][j][r] = 0.f;
-  }
-
-  // how far the zero padding of each orientation reaches inside this tile
-  const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
-  const int dz_cols = (int)min((int64_t)BM, a.ldz - v0);     // dz[token][vocab]:  token < N, vocab < ldz
-
-  if constexpr (sizeof(st) == 2) {
-    // bf16: pack pairs of consecutive vocab rows first (the fp32 values die here), then stage each orientation
-    // through LDS so that global stores are full 16-byte chunks of contiguous rows.
-    uint32_t pk[TM][TN][8];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int p = 0; p < 8; ++p) pk[i][j][p] = pack_bf16(acc[i][j][2 * p], acc[i][j][2 * p + 1]);
-    __syncthreads();                                         // main-loop LDS reads are over: reuse smem
-    uint16_t* stage = reinterpret_cast<uint16_t*>(smem);
-    // token-major: stage[token][vocab]; a lane holds 4 consecutive vocab rows of one token = 8 bytes
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          uint2 v;
-          v.x = pk[i][j][2 * q4];
-          v.y = pk[i][j][2 * q4 + 1];
-          *reinterpret_cast<uint2*>(stage + lp.col(j) * STAGE_LD + lp.row(i, q4 * 4)) = v;
-        }
-    __syncthreads();
-    uint16_t* dz = reinterpret_cast<uint16_t*>(a.dz);
-    for (int q = tid; q < BN * (BM / 8); q += NTHREADS) {
-      const int tok = q >> 5, ch = q & 31;
-      if (tok < rowsT && ch * 8 < dz_cols) {
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + tok * STAGE_LD + ch * 8);
-        *reinterpret_cast<uint4*>(dz + (t0 + tok) * a.ldz + v0 + ch * 8) = v;
-      }
-    }
-    __syncthreads();
-    // vocab-major: stage[vocab][token]; lanes of a half-wave hold 32 consecutive tokens
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          stage[lp.row(i, 2 * p) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] & 0xffffu);
-          stage[lp.row(i, 2 * p + 1) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] >> 16);
-        }
-    __syncthreads();
-    uint16_t* dzt = reinterpret_cast<uint16_t*>(a.dzt);
-    for (int q = tid; q < BM * (BN / 8); q += NTHREADS) {
-      const int vr = q >> 5, ch = q & 31;
-      if (vr < rowsV && ch * 8 < dzt_cols) {
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + vr * STAGE_LD + ch * 8);
-        *reinterpret_cast<uint4*>(dzt + (v0 + vr) * a.ldzt + t0 + ch * 8) = v;
-      }
-    }
-  } else {
-    float* dz = reinterpret_cast<float*>(a.dz);
-    float* dzt = reinterpret_cast<float*>(a.dzt);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int vr = lp.row(i, r), tok = lp.col(j);
-          if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = acc[i][j][r];
-          if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = acc[i][j][r];
+          const float p = fast_exp2(fmaf(acc[i][j][r], LOG2E, -lb));
+          acc[i][j][r] = live ? -c * p : 0.f;
         }
+      // + coef at the target's own vocab row: one lane of one wave of one vocab tile per token
+      const bool mine = live && yrel >= 0 && yrel < WAVE_M && (yrel & 4) == 0;
+      if (__any(mine)) {                                     // wave-uniform
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            acc[i][j][r] += (mine && yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? c : 0.f;
+      }
+    }
+    if (rowsV < BM) {   // last vocab tile only (block-uniform): padded vocab rows are 0
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (lp.row(i, r) >= rowsV) acc[i][j][r] = 0.f;
+    }
+
+    // how far the zero padding of each orientation reaches inside this tile
+    const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
+    const int dz_cols = (int)min((int64_t)BM, a.ldz - v0);     // dz[token][vocab]:  token < N, vocab < ldz
+
+    if constexpr (sizeof(st) == 2) {
+      // bf16: pack pairs of consecutive vocab rows first (the fp32 values die here), then stage each orientation
+      // through LDS so that global stores are full 16-byte chunks of contiguous rows.
+      uint32_t pk[TM][TN][8];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int p = 0; p < 8; ++p) pk[i][j][p] = pack_bf16(acc[i][j][2 * p], acc[i][j][2 * p + 1]);
+      __syncthreads();                                         // main-loop LDS reads are over: reuse smem
+      uint16_t* stage = reinterpret_cast<uint16_t*>(smem);
+      // token-major: stage[token][vocab]; a lane holds 4 consecutive vocab rows of one token = 8 bytes
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            uint2 v;
+            v.x = pk[i][j][2 * q4];
+            v.y = pk[i][j][2 * q4 + 1];
+            *reinterpret_cast<uint2*>(stage + lp.col(j) * STAGE_LD + lp.row(i, q4 * 4)) = v;
+          }
+      __syncthreads();
+      uint16_t* dz = reinterpret_cast<uint16_t*>(a.dz);
+      for (int q = tid; q < BN * (BM / 8); q += NTHREADS) {
+        const int tok = q >> 5, ch = q & 31;
+        if (tok < rowsT && ch * 8 < dz_cols) {
+          const uint4 v = *reinterpret_cast<const uint4*>(stage + tok * STAGE_LD + ch * 8);
+          *reinterpret_cast<uint4*>(dz + (t0 + tok) * a.ldz + v0 + ch * 8) = v;
+        }
+      }
+      __syncthreads();
+      // vocab-major: stage[vocab][token]; lanes of a half-wave hold 32 consecutive tokens
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int p = 0; p < 8; ++p) {
+            stage[lp.row(i, 2 * p) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] & 0xffffu);
+            stage[lp.row(i, 2 * p + 1) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] >> 16);
+          }
+      __syncthreads();
+      uint16_t* dzt = reinterpret_cast<uint16_t*>(a.dzt);
+      for (int q = tid; q < BM * (BN / 8); q += NTHREADS) {
+        const int vr = q >> 5, ch = q & 31;
+        if (vr < rowsV && ch * 8 < dzt_cols) {
+          const uint4 v = *reinterpret_cast<const uint4*>(stage + vr * STAGE_LD + ch * 8);
+          *reinterpret_cast<uint4*>(dzt + (v0 + vr) * a.ldzt + t0 + ch * 8) = v;
+        }
+      }
+    } else {
+      float* dz = reinterpret_cast<float*>(a.dz);
+      float* dzt = reinterpret_cast<float*>(a.dzt);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int vr = lp.row(i, r), tok = lp.col(j);
+            if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = acc[i][j][r];
+            if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = acc[i][j][r];
+          }
+    }
+    __syncthreads();                                           // staging reads are over before the next prefetch
   }
 }
 
@@ -361,71 +409,113 @@ struct StoreArgs {
 };
 
 template <typename TT>
+struct StoreTile {     // what one tile of k_gemm_store contracts and where it goes
+  int64_t row0, col0, k_lo, k_len;
+  int rowsA, rowsB, split;
+  __device__ __forceinline__ void set(const StoreArgs& a, int tiles_m, int64_t M, int64_t K, int tms, int tn) {
+    constexpr int BK = 8 * TT::EPC;
+    split = tms / tiles_m;                           // split-major ids: tiles of one K range run together
+    row0 = (int64_t)(tms - split * tiles_m) * BM;
+    col0 = (int64_t)tn * BN;
+    rowsA = (int)min((int64_t)BM, M - row0);
+    rowsB = (int)min((int64_t)BN, a.Nn - col0);
+    const int nk = (int)((K + BK - 1) / BK);         // 32-bit: slabs per contraction fit an int by far
+    k_lo = (int64_t)(nk * split / a.splits) * BK;
+    k_len = min(K, (int64_t)(nk * (split + 1) / a.splits) * BK) - k_lo;
+  }
+};
+
+template <typename TT>
+__device__ __forceinline__ StoreTile<TT> store_tile_of(const TileSchedule& sch, const StoreArgs& a, int id, int tiles_m,
+                                                       int64_t M, int64_t K) {
+  StoreTile<TT> t;
+  int tms, tn;
+  sch.coords(id, tms, tn);
+  t.set(a, tiles_m, M, K, tms, tn);
+  return t;
+}
+template <typename TT>
+__device__ __forceinline__ void store_fetch(TileGemm<TT>& g, const TileSchedule& sch, const StoreArgs& a, int id,
+                                            int tiles_m, int64_t M, int64_t K, char* smem) {
+  typedef typename TT::store_t st;
+  const StoreTile<TT> t = store_tile_of<TT>(sch, a, id, tiles_m, M, K);
+  if (t.k_len > 0)
+    g.template prefetch<false>((const st*)a.A + t.row0 * a.lda + t.k_lo, a.lda, t.rowsA,
+                               (const st*)a.B + t.col0 * a.ldb + t.k_lo, a.ldb, t.rowsB, t.k_len, smem);
+}
+
+template <typename TT>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  typedef typename TT::store_t st;
   const int64_t M = a.m_count ? (int64_t)*a.m_count : a.M;
   const int64_t K = a.k_count ? ((int64_t)*a.k_count + 63) / 64 * 64 : a.K;
   const int tiles_m = (int)((M + BM - 1) / BM);
-  int tms, tn;
-  // split-major ids: all tiles of one K range run together and share operand panels in L2
-  if (!tile_coords(tiles_m * a.splits, a.tiles_n, tms, tn)) return;     // block-uniform
-  const int split = tms / tiles_m, tm = tms - split * tiles_m;
-  const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-  const int rowsA = (int)min((int64_t)BM, M - row0);
-  const int rowsB = (int)min((int64_t)BN, a.Nn - col0);
-  typedef typename TT::store_t st;
-  constexpr int BK = 8 * TT::EPC;
-  const int64_t nk = (K + BK - 1) / BK;
-  const int64_t k_lo = nk * split / a.splits * BK, k_hi = min(K, nk * (split + 1) / a.splits * BK);
-  f32x16_t acc[TM][TN];
-  if (k_hi > k_lo) {
-    gemm_nt_mainloop<TT>((const st*)a.A + row0 * a.lda + k_lo, a.lda, rowsA, (const st*)a.B + col0 * a.ldb + k_lo,
-                         a.ldb, rowsB, k_hi - k_lo, smem, acc);
-  } else {                                           // nothing to contract: the product is zero
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  }
+  TileSchedule sch;
+  sch.init(tiles_m * a.splits, a.tiles_n);
+  if (!sch.has_tile()) return;                       // block-uniform
   const int tid = threadIdx.x;
-  LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
-  if (a.splits > 1) {                                // fp32 partial slice, rows by list position
-    float* C = reinterpret_cast<float*>(a.C) + (int64_t)split * a.split_stride;
+  const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  TileGemm<TT> g;
+  int id = sch.take();
+  store_fetch<TT>(g, sch, a, id, tiles_m, M, K, smem);
+  while (true) {
+    f32x16_t acc[TM][TN];
+    const int cur_id = id;
+    if (store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K).k_len > 0) {
+      g.run(smem, acc);
+    } else {                                         // nothing to contract: the product is zero
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rib = lp.row(i, r), cib = lp.col(j);
-          if (rib < rowsA && cib < rowsB) C[(row0 + rib) * a.ldc + col0 + cib] = acc[i][j][r];
-        }
-    return;
-  }
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    }
+    const bool more = sch.has_tile();
+    __syncthreads();                                 // every wave is done reading the slab buffers
+    if (more) {                                      // the store epilogue uses no LDS: fetch the next tile under it
+      id = sch.take();
+      store_fetch<TT>(g, sch, a, id, tiles_m, M, K, smem);
+    }
+    const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
+    // Store epilogue, one 32-row block at a time (fences keep the unrolled blocks from piling up address registers).
+    // mode 0: fp32 split-K partial slice; 1: fp32; 2: fp32 accumulate; 3: bf16; 4: bf16 accumulate.
+    const int mode = a.splits > 1 ? 0 : (a.c_is_f32 ? (a.accumulate ? 2 : 1) : (a.accumulate ? 4 : 3));
+    char* Cb = reinterpret_cast<char*>(a.C);
+    if (mode == 0) Cb += (int64_t)cur.split * a.split_stride * 4;
+    const int esz = (mode >= 3) ? 2 : 4;
+    const bool scatter = (mode != 0) && a.c_rows != nullptr;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int i = 0; i < TM; ++i) {
+      LLAMARL_FENCE();
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int rib = lp.row(i, r), cib = lp.col(j);
-        if (rib < rowsA && cib < rowsB) {
-          const int64_t crow = a.c_rows ? (int64_t)a.c_rows[row0 + rib] : row0 + rib;
-          const int64_t idx = crow * a.ldc + col0 + cib;
-          float v = acc[i][j][r];
-          if (a.c_is_f32) {
-            float* C = reinterpret_cast<float*>(a.C);
-            if (a.accumulate) v += C[idx];
-            C[idx] = v;
-          } else {
-            uint16_t* C = reinterpret_cast<uint16_t*>(a.C);
-            if (a.accumulate) v += bf16_bits_to_float(C[idx]);
-            C[idx] = float_to_bf16_bits(v);
+        const int rib = lp.row(i, r);
+        if (rib < cur.rowsA) {
+          const int64_t crow = scatter ? (int64_t)a.c_rows[cur.row0 + rib] : cur.row0 + rib;
+          char* rowp = Cb + (crow * a.ldc + cur.col0) * esz;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int cib = lp.col(j);
+            if (cib < cur.rowsB) {
+              float v = acc[i][j][r];
+              if (mode <= 2) {
+                float* q = reinterpret_cast<float*>(rowp) + cib;
+                if (mode == 2) v += *q;
+                *q = v;
+              } else {
+                uint16_t* q = reinterpret_cast<uint16_t*>(rowp) + cib;
+                if (mode == 4) v += bf16_bits_to_float(*q);
+                *q = float_to_bf16_bits(v);
+              }
+            }
           }
         }
       }
+    }
+    if (!more) break;
+  }
 }
 
 // out[rows[p]][c] = sum over splits (ascending) of part[s][p][c], p < *m_count; 4 columns per thread.

@@ -118,6 +118,20 @@ hipError_t set_lds(K kernel, int bytes) {
                              bytes);
 }
 
+// One persistent workgroup per CU (256 on MI355X); a smaller problem gets one workgroup per tile.
+int persistent_grid(int64_t tiles) {
+  static int cus = 0;   // a device property, not call state: read once
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return (int)(tiles < (int64_t)cus ? tiles : (int64_t)cus);
+}
+
 #define HIP_TRY(expr)                                                                              \
   do {                                                                                             \
     hipError_t e_ = (expr);                                                                        \
@@ -136,7 +150,8 @@ llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int6
   a.tiles_n = (int)((Nn + BN - 1) / BN);
   a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
   HIP_TRY(set_lds(k_gemm_store<TT>, MAINLOOP_LDS_BYTES));
-  k_gemm_store<TT><<<dim3((unsigned)(tiles_m * a.tiles_n * splits)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
+  k_gemm_store<TT><<<dim3((unsigned)persistent_grid((int64_t)tiles_m * a.tiles_n * splits)), dim3(NTHREADS),
+                     MAINLOOP_LDS_BYTES, st>>>(a);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
@@ -157,8 +172,9 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
   // active-token list (mask and target range); inactive rows get logp = lse = 0 here
   k_compact_rows<<<dim3(1), dim3(1024), 0, st>>>(0, mask, targets, V, nullptr, N, rows, n_act, logp, lse);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(set_lds(k_fwd_partials<TT>, MAINLOOP_LDS_BYTES));
-  k_fwd_partials<TT><<<dim3((unsigned)(w.tiles_v * w.tiles_t)), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
+  HIP_TRY(set_lds(k_fwd_partials<TT>, FWD_LDS_BYTES));
+  k_fwd_partials<TT><<<dim3((unsigned)persistent_grid((int64_t)w.tiles_v * w.tiles_t)), dim3(NTHREADS), FWD_LDS_BYTES,
+                       st>>>(a);
   HIP_TRY(hipGetLastError());
   k_merge_logp<<<dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, rows, n_act,
                                                                      w.tiles_v, w.n_pad, logp, lse);
@@ -201,7 +217,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt; a.rows = rows; a.n_act = n_act;
   const int dz_lds = sizeof(stt) == 2 ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES;
   HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
-  k_bwd_dz<TT><<<dim3((unsigned)(a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
+  k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
   HIP_TRY(hipGetLastError());
 
   // dH [active rows, d] = dz [n_act,V] . W^T[d,V]^T    (K = V, zero-padded to ldz), scattered to the token rows
