@@ -4,7 +4,8 @@
 //                    target logit: the [N,V] logits never leave the accumulators (paper Sec. 6: log pi(y_t|.))
 //   k_merge_logp     partials -> lse[t], logp[t]
 //   k_bwd_dz         recomputed logits tile -> dz = g * coef * (onehot - softmax), written in both orientations
-//   k_gemm_store     plain C = A B^T with a store epilogue (dH and dW)
+//   k_gemm_store     plain contraction with a store epilogue: dW = dz^T H (K-contiguous operands) and
+//                    dH = dz W (k-major operands: dz^T as written, W as the caller holds it; bf16)
 //   k_transpose      [R,C] -> [C,R] with zero padding (W^T and H^T panels for the two backward contractions)
 //
 // In the two logits kernels the MFMA "row" operand is W (vocab) and the "column" operand is H (tokens): an
@@ -12,6 +13,9 @@
 // softmax reductions over the vocabulary run inside the lane's own registers, with a single cross-lane step.
 #pragma once
 #include "gemm_nt.h"
+#include "gemm_tn.h"
+
+#include <type_traits>
 
 namespace llamarl {
 
@@ -267,15 +271,16 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
   TileGemm<TT> g;
   while (sch.has_tile()) {
+    const int id = sch.take();
+    // the bf16 epilogue stages the whole tile through LDS, so the next tile cannot be fetched under it
+    fwd_fetch<TT>(g, sch, a, id, n_act, smem);
+    f32x16_t acc[TM][TN];
+    g.run(smem, acc);
     int tv, tt;
-    sch.coords(sch.take(), tv, tt);
+    sch.coords(id, tv, tt);
     const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
     const int rowsV = (int)min((int64_t)BM, a.V - v0);
     const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
-    // the bf16 epilogue stages the whole tile through LDS, so the next tile cannot be fetched under it
-    g.template prefetch<true>((const st*)a.W + v0 * a.d, a.d, rowsV, a.H, a.d, rowsT, a.d, smem, a.rows + t0, a.N);
-    f32x16_t acc[TM][TN];
-    g.run(smem, acc);
 
     // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
     const int lane_row0 = lp.row(0, 0);
@@ -305,23 +310,12 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
             acc[i][j][r] += (mine && yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? c : 0.f;
       }
     }
-    if (rowsV < BM) {   // last vocab tile only (block-uniform): padded vocab rows are 0
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (lp.row(i, r) >= rowsV) acc[i][j][r] = 0.f;
-    }
 
     // how far the zero padding of each orientation reaches inside this tile
     const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
-    const int dz_cols = (int)min((int64_t)BM, a.ldz - v0);     // dz[token][vocab]:  token < N, vocab < ldz
-
     if constexpr (sizeof(st) == 2) {
-      // bf16: pack pairs of consecutive vocab rows first (the fp32 values die here), then stage each orientation
-      // through LDS so that global stores are full 16-byte chunks of contiguous rows.
+      // bf16: only the vocab-major orientation exists (both gradient contractions read it).  Pack pairs of rows
+      // (the fp32 values die here) and stage the tile through LDS so that it leaves as 16-byte chunks of rows.
       uint32_t pk[TM][TN][8];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -330,30 +324,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
 #pragma unroll
           for (int p = 0; p < 8; ++p) pk[i][j][p] = pack_bf16(acc[i][j][2 * p], acc[i][j][2 * p + 1]);
       __syncthreads();                                         // main-loop LDS reads are over: reuse smem
-      uint16_t* stage = reinterpret_cast<uint16_t*>(smem);
-      // token-major: stage[token][vocab]; a lane holds 4 consecutive vocab rows of one token = 8 bytes
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            uint2 v;
-            v.x = pk[i][j][2 * q4];
-            v.y = pk[i][j][2 * q4 + 1];
-            *reinterpret_cast<uint2*>(stage + lp.col(j) * STAGE_LD + lp.row(i, q4 * 4)) = v;
-          }
-      __syncthreads();
-      uint16_t* dz = reinterpret_cast<uint16_t*>(a.dz);
-      for (int q = tid; q < BN * (BM / 8); q += NTHREADS) {
-        const int tok = q >> 5, ch = q & 31;
-        if (tok < rowsT && ch * 8 < dz_cols) {
-          const uint4 v = *reinterpret_cast<const uint4*>(stage + tok * STAGE_LD + ch * 8);
-          *reinterpret_cast<uint4*>(dz + (t0 + tok) * a.ldz + v0 + ch * 8) = v;
-        }
-      }
-      __syncthreads();
-      // vocab-major: stage[vocab][token]; lanes of a half-wave hold 32 consecutive tokens
+      uint16_t* stage = reinterpret_cast<uint16_t*>(smem);     // stage[vocab][token]
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -372,7 +343,9 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
           *reinterpret_cast<uint4*>(dzt + (v0 + vr) * a.ldzt + t0 + ch * 8) = v;
         }
       }
+      __syncthreads();                                         // staging reads are over before the next prefetch
     } else {
+      const int dz_cols = (int)min((int64_t)BM, a.ldz - v0);   // dz[token][vocab]:  token < N, vocab < ldz
       float* dz = reinterpret_cast<float*>(a.dz);
       float* dzt = reinterpret_cast<float*>(a.dzt);
 #pragma unroll
@@ -382,11 +355,11 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int vr = lp.row(i, r), tok = lp.col(j);
-            if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = acc[i][j][r];
-            if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = acc[i][j][r];
+            const float v = (vr < rowsV) ? acc[i][j][r] : 0.f;   // padded vocab rows of the token-major copy are 0
+            if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = v;
+            if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = v;
           }
     }
-    __syncthreads();                                           // staging reads are over before the next prefetch
   }
 }
 
@@ -443,8 +416,16 @@ __device__ __forceinline__ void store_fetch(TileGemm<TT>& g, const TileSchedule&
     g.template prefetch<false>((const st*)a.A + t.row0 * a.lda + t.k_lo, a.lda, t.rowsA,
                                (const st*)a.B + t.col0 * a.ldb + t.k_lo, a.ldb, t.rowsB, t.k_len, smem);
 }
+// k-major operands: A is At [K][lda] (output rows are its columns), B is Bt [K][ldb]
+__device__ __forceinline__ void store_fetch(TileGemmTN& g, const TileSchedule& sch, const StoreArgs& a, int id,
+                                            int tiles_m, int64_t M, int64_t K, char* smem) {
+  const StoreTile<BF16> t = store_tile_of<BF16>(sch, a, id, tiles_m, M, K);
+  if (t.k_len > 0)
+    g.prefetch((const uint16_t*)a.A + t.k_lo * a.lda + t.row0, a.lda, t.row0,
+               (const uint16_t*)a.B + t.k_lo * a.ldb + t.col0, a.ldb, t.col0, (int)t.k_len, smem);
+}
 
-template <typename TT>
+template <typename TT, bool KMAJOR>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   typedef typename TT::store_t st;
@@ -456,9 +437,9 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   if (!sch.has_tile()) return;                       // block-uniform
   const int tid = threadIdx.x;
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
-  TileGemm<TT> g;
+  typename std::conditional<KMAJOR, TileGemmTN, TileGemm<TT>>::type g;
   int id = sch.take();
-  store_fetch<TT>(g, sch, a, id, tiles_m, M, K, smem);
+  store_fetch(g, sch, a, id, tiles_m, M, K, smem);
   while (true) {
     f32x16_t acc[TM][TN];
     const int cur_id = id;
@@ -476,7 +457,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // the store epilogue uses no LDS: fetch the next tile under it
       id = sch.take();
-      store_fetch<TT>(g, sch, a, id, tiles_m, M, K, smem);
+      store_fetch(g, sch, a, id, tiles_m, M, K, smem);
     }
     const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
     // Store epilogue, one 32-row block at a time (fences keep the unrolled blocks from piling up address registers).

@@ -75,10 +75,13 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
   const size_t es = esize(dt);
   w.ldz = round_up(V, 64);
   w.ldzt = round_up(N, 64);
+  // bf16: dz exists in the vocab-major orientation only and W is read as it is (k-major dH contraction);
+  // fp32 keeps a token-major dz and a transposed copy of W as well
+  const bool both = dt == LLAMARL_F32;
   w.off_dz = 0;
-  w.off_dzt = w.off_dz + (size_t)round_up(N * w.ldz * (int64_t)es, 256);
+  w.off_dzt = w.off_dz + (both ? (size_t)round_up(N * w.ldz * (int64_t)es, 256) : 0);
   w.off_wt = w.off_dzt + (size_t)round_up(V * w.ldzt * (int64_t)es, 256);
-  w.off_ht = w.off_wt + (size_t)round_up(d * w.ldz * (int64_t)es, 256);
+  w.off_ht = w.off_wt + (both ? (size_t)round_up(d * w.ldz * (int64_t)es, 256) : 0);
   w.off_rows = w.off_ht + (size_t)round_up(d * w.ldzt * (int64_t)es, 256);
   w.off_nact = w.off_rows + (size_t)round_up(w.ldzt * (int64_t)sizeof(int32_t), 256);
   w.off_part = w.off_nact + 256;
@@ -138,7 +141,7 @@ int persistent_grid(int64_t tiles) {
     if (e_ != hipSuccess) return fail(LLAMARL_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
-template <typename TT>
+template <typename TT, bool KMAJOR = false>
 llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t Nn,
                                  int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, const int32_t* m_count,
                                  const int32_t* k_count, const int32_t* c_rows, int splits, int64_t split_stride,
@@ -149,9 +152,9 @@ llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int6
   const int tiles_m = (int)((M + BM - 1) / BM);      // worst case: every row active
   a.tiles_n = (int)((Nn + BN - 1) / BN);
   a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
-  HIP_TRY(set_lds(k_gemm_store<TT>, MAINLOOP_LDS_BYTES));
-  k_gemm_store<TT><<<dim3((unsigned)persistent_grid((int64_t)tiles_m * a.tiles_n * splits)), dim3(NTHREADS),
-                     MAINLOOP_LDS_BYTES, st>>>(a);
+  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR>, MAINLOOP_LDS_BYTES));
+  k_gemm_store<TT, KMAJOR><<<dim3((unsigned)persistent_grid((int64_t)tiles_m * a.tiles_n * splits)), dim3(NTHREADS),
+                             MAINLOOP_LDS_BYTES, st>>>(a);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
@@ -201,39 +204,48 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   k_zero_inactive_rows<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(reinterpret_cast<stt*>(dH), coef, N, d);
   HIP_TRY(hipGetLastError());
 
-  // operand panels for the two gradient contractions: W^T [d][ldz], and H^T [d][ldzt] of the active tokens only
-  k_transpose<stt><<<dim3((unsigned)(w.ldz / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
-      reinterpret_cast<const stt*>(W), V, d, d, wt, w.ldz, nullptr, nullptr);
-  HIP_TRY(hipGetLastError());
+  constexpr bool kBf16 = sizeof(stt) == 2;
+  // operand panels: H^T [d][ldzt] of the active tokens (dW contraction); fp32 also needs W^T [d][ldz]
+  if (!kBf16) {
+    k_transpose<stt><<<dim3((unsigned)(w.ldz / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
+        reinterpret_cast<const stt*>(W), V, d, d, wt, w.ldz, nullptr, nullptr);
+    HIP_TRY(hipGetLastError());
+  }
   k_transpose<stt><<<dim3((unsigned)(w.ldzt / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
       reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, rows, n_act);
   HIP_TRY(hipGetLastError());
 
-  // recompute logits tile by tile, turn them into dz in both orientations (rows / columns = list positions)
+  // recompute logits tile by tile, turn them into dz (rows / columns = list positions)
   DzArgs a;
   a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
   a.tiles_v = (int)((V + BM - 1) / BM);
   a.tiles_t = (int)((N + BN - 1) / BN);
   a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt; a.rows = rows; a.n_act = n_act;
-  const int dz_lds = sizeof(stt) == 2 ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES;
+  const int dz_lds = kBf16 ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES;
   HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
   k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
   HIP_TRY(hipGetLastError());
 
-  // dH [active rows, d] = dz [n_act,V] . W^T[d,V]^T    (K = V, zero-padded to ldz), scattered to the token rows
+  // dH [active rows, d] = dz [n_act,V] . W [V,d], scattered to the token rows.
+  //   bf16: k-major operands dz^T [V][n_act] and W [V][d], K = V exactly
+  //   fp32: K-contiguous operands dz [n_act][ldz] and W^T [d][ldz], K zero-padded to ldz
   llamarl_status s;
+  float* part = reinterpret_cast<float*>(ws + w.off_part);
+  void* dh_out = w.dh_splits > 1 ? static_cast<void*>(part) : dH;
+  const int dh_f32 = w.dh_splits > 1 ? 1 : (dt == LLAMARL_F32);
+  const int32_t* dh_scatter = w.dh_splits > 1 ? nullptr : rows;
+  if constexpr (kBf16) {
+    s = launch_store_gemm<TT, true>(dzt, w.ldzt, W, d, N, d, V, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
+                                    w.dh_splits, N * d, st);
+  } else {
+    s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
+                              w.dh_splits, N * d, st);
+  }
+  if (s != LLAMARL_OK) return s;
   if (w.dh_splits > 1) {
-    float* part = reinterpret_cast<float*>(ws + w.off_part);
-    s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, part, d, 1, 0, n_act, nullptr, nullptr, w.dh_splits,
-                              N * d, st);
-    if (s != LLAMARL_OK) return s;
     k_reduce_splits<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(part, w.dh_splits, N * d, rows, n_act, d,
                                                                  reinterpret_cast<stt*>(dH), d);
     HIP_TRY(hipGetLastError());
-  } else {
-    s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dH, d, dt == LLAMARL_F32, 0, n_act, nullptr, rows, 1,
-                              0, st);
-    if (s != LLAMARL_OK) return s;
   }
   // dW [V,d] = dz^T [V,n_act] . H^T[d,n_act]^T          (K = n_act, zero-padded to a multiple of 64)
   return launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW,

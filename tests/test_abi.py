@@ -39,8 +39,8 @@ def test_workspace_sizes(clib):
     assert small >= 3 * 256 * 4 and small % 256 == 0
     assert wb(16384, 4096, 128256, binding.BF16, binding.PASS_LOGPROBS) >= 2 * 501 * 16384 * 4
     b = wb(16384, 4096, 128256, binding.BF16, binding.PASS_LOSS_BWD)
-    assert b >= 2 * 16384 * 128256 * 2 + 4096 * (128256 + 16384) * 2
-    assert wb(16384, 4096, 128256, binding.F32, binding.PASS_LOSS_BWD) >= 1.8 * b
+    assert b >= 16384 * 128256 * 2 + 4096 * 16384 * 2          # dz^T and H^T panels at least
+    assert wb(16384, 4096, 128256, binding.F32, binding.PASS_LOSS_BWD) >= 2 * 16384 * 128256 * 4
     assert wb(1000, 0, 0, 0, binding.PASS_LOSS_FWD) >= 8 * 1000
 
 
