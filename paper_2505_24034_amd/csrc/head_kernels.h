@@ -425,7 +425,9 @@ __device__ __forceinline__ void store_fetch(TileGemmTN& g, const TileSchedule& s
                (const uint16_t*)a.B + t.k_lo * a.ldb + t.col0, a.ldb, t.col0, (int)t.k_len, smem);
 }
 
-template <typename TT, bool KMAJOR>
+// MODE (compile time, so each instantiation carries one epilogue only):
+//   0 fp32 split-K partial slice   1 fp32   2 fp32 accumulate   3 bf16   4 bf16 accumulate
+template <typename TT, bool KMAJOR, int MODE>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   typedef typename TT::store_t st;
@@ -461,12 +463,37 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
     }
     const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
     // Store epilogue, one 32-row block at a time (fences keep the unrolled blocks from piling up address registers).
-    // mode 0: fp32 split-K partial slice; 1: fp32; 2: fp32 accumulate; 3: bf16; 4: bf16 accumulate.
-    const int mode = a.splits > 1 ? 0 : (a.c_is_f32 ? (a.accumulate ? 2 : 1) : (a.accumulate ? 4 : 3));
+    constexpr int mode = MODE;
     char* Cb = reinterpret_cast<char*>(a.C);
     if (mode == 0) Cb += (int64_t)cur.split * a.split_stride * 4;
     const int esz = (mode >= 3) ? 2 : 4;
     const bool scatter = (mode != 0) && a.c_rows != nullptr;
+    if (mode == 3 && !scatter && cur.rowsB == BN) {
+      // bf16, full-width tile: neighbouring lanes hold neighbouring columns of the same rows.  Lane pairs swap
+      // one value each (DPP quad_perm 1,0,3,2) so that the even lane owns columns (c, c+1) of row r and the odd lane
+      // the same two columns of row r+1: one v_cvt_pk_bf16_f32 and one 4-byte store per two elements.
+      const bool odd = lp.lane & 1;
+      uint16_t* C = reinterpret_cast<uint16_t*>(a.C);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        LLAMARL_FENCE();
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const int rib = lp.row(i, 2 * p) + (odd ? 1 : 0);
+          uint16_t* rowp = C + (cur.row0 + rib) * a.ldc + cur.col0;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const float own0 = acc[i][j][2 * p], own1 = acc[i][j][2 * p + 1];
+            const float nbr0 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(own0), 0xB1, 0xF, 0xF, true));
+            const float nbr1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(own1), 0xB1, 0xF, 0xF, true));
+            const uint32_t v = pack_bf16(odd ? nbr1 : own0, odd ? own1 : nbr0);
+            if (rib < cur.rowsA) *reinterpret_cast<uint32_t*>(rowp + (lp.col(j) & ~1)) = v;
+          }
+        }
+      }
+      if (!more) break;
+      continue;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       LLAMARL_FENCE();

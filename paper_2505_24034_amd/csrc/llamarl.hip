@@ -141,6 +141,15 @@ int persistent_grid(int64_t tiles) {
     if (e_ != hipSuccess) return fail(LLAMARL_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
+template <typename TT, bool KMAJOR, int MODE>
+llamarl_status launch_store_mode(const StoreArgs& a, int64_t work_items, hipStream_t st) {
+  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR, MODE>, MAINLOOP_LDS_BYTES));
+  k_gemm_store<TT, KMAJOR, MODE><<<dim3((unsigned)persistent_grid(work_items)), dim3(NTHREADS), MAINLOOP_LDS_BYTES,
+                                   st>>>(a);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
 template <typename TT, bool KMAJOR = false>
 llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t Nn,
                                  int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, const int32_t* m_count,
@@ -152,11 +161,15 @@ llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int6
   const int tiles_m = (int)((M + BM - 1) / BM);      // worst case: every row active
   a.tiles_n = (int)((Nn + BN - 1) / BN);
   a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
-  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR>, MAINLOOP_LDS_BYTES));
-  k_gemm_store<TT, KMAJOR><<<dim3((unsigned)persistent_grid((int64_t)tiles_m * a.tiles_n * splits)), dim3(NTHREADS),
-                             MAINLOOP_LDS_BYTES, st>>>(a);
-  HIP_TRY(hipGetLastError());
-  return LLAMARL_OK;
+  const int64_t items = (int64_t)tiles_m * a.tiles_n * splits;
+  if (splits > 1) return launch_store_mode<TT, KMAJOR, 0>(a, items, st);
+  if (c_is_f32) return accumulate ? launch_store_mode<TT, KMAJOR, 2>(a, items, st)
+                                  : launch_store_mode<TT, KMAJOR, 1>(a, items, st);
+  if constexpr (sizeof(typename TT::store_t) == 2) {
+    return accumulate ? launch_store_mode<TT, KMAJOR, 4>(a, items, st) : launch_store_mode<TT, KMAJOR, 3>(a, items, st);
+  } else {
+    return fail(LLAMARL_ERR_INVALID_ARG, "a 16-bit output needs a 16-bit input type");
+  }
 }
 
 template <typename TT>
