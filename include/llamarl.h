@@ -22,8 +22,10 @@
  *    llamarl_last_error() then returns a message (thread-local storage).
  *  - Pointers must be 16-byte aligned (anything hipMalloc/torch returns is).
  *  - dtype LLAMARL_BF16 needs d % 8 == 0, LLAMARL_F32 needs d % 4 == 0
- *    (16-byte rows).  N, V are arbitrary (>= 1).  N*d, V*d element counts may
- *    exceed 2^32 bytes; single rows may not.
+ *    (16-byte rows).  N, V are arbitrary (>= 1).  W may exceed 4 GiB; H must be
+ *    smaller than 2 GiB (its rows are gathered with 32-bit offsets) and a
+ *    256-row panel of any operand smaller than 2 GiB: LLAMARL_ERR_UNSUPPORTED
+ *    otherwise.
  *  - Results are deterministic: the same inputs give the same bits, run to run
  *    (no floating-point atomics anywhere).
  */
@@ -156,6 +158,20 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
                                           llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Group-mean baseline (Sec. 6: from one prompt, n generations are sampled and the baseline is the mean of their
+ * rewards, constant over the tokens of a generation):
+ *     adv[p,i] = r[p,i] - (1/n) sum_j r[p,j]
+ * With normalise_std != 0 the result is also divided by (population std of the group + eps), the group
+ * normalisation GRPO uses (the paper cites it; its own baseline is the plain mean).
+ *
+ *   rewards  in  float [P*n], generation i of prompt p at p*n + i
+ *   adv      out float [P*n]  (may alias rewards)
+ * The output is the `adv` argument of llamarl_offpolicy_loss_fwd when generations are stored prompt-major.
+ */
+llamarl_status llamarl_group_advantages(const float* rewards, int64_t P, int64_t n, int normalise_std, float eps,
+                                        float* adv, void* stream);
 
 #ifdef __cplusplus
 }

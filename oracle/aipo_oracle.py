@@ -221,6 +221,18 @@ def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0):
     return dH, dW
 
 
+def group_advantages(rewards, n, normalise_std=False, eps=1e-6):
+    """Group-mean baseline (Sec. 6): from one prompt n generations are sampled and the baseline is the mean of
+    their rewards, constant over a generation's tokens: A_i = r_i - (1/n) sum_j r_j.  With normalise_std the
+    result is divided by (population std of the group + eps) -- the GRPO normalisation the paper cites, not part
+    of its own baseline.  rewards: [P*n] prompt-major.  Returns [P*n]."""
+    r = np.asarray(rewards, dtype=np.float64).reshape(-1, n)
+    a = r - r.mean(axis=1, keepdims=True)
+    if normalise_std:
+        a = a / (np.sqrt((a * a).mean(axis=1, keepdims=True)) + eps)
+    return a.reshape(-1)
+
+
 def aipo_step(H, W, targets, mu_logp, adv, mask, rho, norm_mode=NORM_TOKEN_MEAN, grad_loss=1.0,
               clip_mode=CLIP_AIPO, eps_lo=0.2, eps_hi=0.2):
     """The whole path in order: log-probs, loss, gradients."""

@@ -20,7 +20,7 @@ NORM_TOKEN_MEAN, NORM_SEQ_MEAN, NORM_SUM_T_MEAN_B = 0, 1, 2
 PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
-           "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd")
+           "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_group_advantages")
 
 
 class LlamarlError(RuntimeError):
@@ -59,6 +59,8 @@ def load():
                                                vp, vp, vp, vp, sz, vp]
     lib.llamarl_offpolicy_loss_bwd.restype = ci
     lib.llamarl_offpolicy_loss_bwd.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, ci, vp, vp, ci, ci, vp, sz, vp]
+    lib.llamarl_group_advantages.restype = ci
+    lib.llamarl_group_advantages.argtypes = [vp, i64, i64, ci, cf, vp, vp]
     _lib = lib
     return lib
 
@@ -174,3 +176,16 @@ def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0, dW_dtype=None, d
                                           N, d, V, dt, _ptr(dH), _ptr(dW), _dtype_code(dW), int(bool(accumulate_dW)),
                                           _ptr(ws), ws.numel(), _stream(stream)))
     return dH, dW
+
+
+def group_advantages(rewards, n, normalise_std=False, eps=1e-6, stream=None):
+    """llamarl_group_advantages: rewards [P*n] (prompt-major) -> advantages [P*n]."""
+    lib = load()
+    _need(rewards, torch.float32, "rewards")
+    if n <= 0 or rewards.numel() % n != 0:
+        raise LlamarlError(ERR_INVALID_ARG, "rewards must hold P*n entries")
+    P = rewards.numel() // n
+    adv = torch.empty_like(rewards)
+    _check(lib.llamarl_group_advantages(_ptr(rewards), P, n, int(bool(normalise_std)), float(eps), _ptr(adv),
+                                        _stream(stream)))
+    return adv

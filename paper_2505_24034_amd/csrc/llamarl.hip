@@ -370,4 +370,16 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                       reinterpret_cast<char*>(ws), st);
 }
 
+llamarl_status llamarl_group_advantages(const float* rewards, int64_t P, int64_t n, int normalise_std, float eps,
+                                        float* adv, void* stream) {
+  if (!rewards || !adv) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  if (P <= 0 || n <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "P and n must be positive");
+  if (P >= ((int64_t)1 << 31) * 4) return fail(LLAMARL_ERR_UNSUPPORTED, "too many prompts");
+  if (normalise_std && !(eps >= 0.f)) return fail(LLAMARL_ERR_INVALID_ARG, "eps must be non-negative");
+  k_group_advantages<<<dim3((unsigned)((P + 3) / 4)), dim3(256), 0, reinterpret_cast<hipStream_t>(stream)>>>(
+      rewards, P, n, normalise_std, eps, adv);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
 }  // extern "C"

@@ -194,4 +194,26 @@ __global__ __launch_bounds__(LOSS_THREADS) void k_loss_finish(LossArgs a) {
   }
 }
 
+// One wavefront per prompt: mean (and optionally population std) of its n rewards by shuffles, fp64 accumulation.
+__global__ __launch_bounds__(256) void k_group_advantages(const float* rewards, int64_t P, int64_t n, int normalise_std,
+                                                          float eps, float* adv) {
+  const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (p >= P) return;
+  const float* r = rewards + p * n;
+  double s = 0.0;
+  for (int64_t i = lane; i < n; i += 64) s += (double)r[i];
+  const double mean = wave_sum(s) / (double)n;
+  double scale = 1.0;
+  if (normalise_std) {
+    double q = 0.0;
+    for (int64_t i = lane; i < n; i += 64) {
+      const double dlt = (double)r[i] - mean;
+      q += dlt * dlt;
+    }
+    scale = 1.0 / (sqrt(wave_sum(q) / (double)n) + (double)eps);
+  }
+  for (int64_t i = lane; i < n; i += 64) adv[p * n + i] = (float)(((double)r[i] - mean) * scale);
+}
+
 }  // namespace llamarl

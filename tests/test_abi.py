@@ -105,6 +105,14 @@ def test_loss_bwd_rejects_bad_arguments(clib):
     assert call(N=-1) == binding.ERR_INVALID_ARG
 
 
+@no_gpu_only
+def test_group_advantages_rejects_bad_arguments(clib):
+    vp = ctypes.c_void_p
+    assert clib.llamarl_group_advantages(None, 2, 2, 0, 0.0, vp(1 << 20), None) == binding.ERR_INVALID_ARG
+    assert clib.llamarl_group_advantages(vp(1 << 20), 0, 2, 0, 0.0, vp(1 << 21), None) == binding.ERR_INVALID_ARG
+    assert clib.llamarl_group_advantages(vp(1 << 20), 2, 2, 1, -1.0, vp(1 << 21), None) == binding.ERR_INVALID_ARG
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libllamarl.so")

@@ -155,3 +155,16 @@ def test_loss_kernel_alone_fp32_exactness_and_infinite_rho(lib):
         assert st[0] == ref["stats"][0]
         if math.isfinite(ref["stats"][1]):
             assert np.allclose(st[1:4], ref["stats"][1:4], rtol=1e-5, atol=1e-6)
+
+
+def test_group_advantages(lib):
+    from oracle import aipo_oracle as orc
+    g = torch.Generator(device="cuda").manual_seed(21)
+    for P, n in ((1, 1), (5, 8), (300, 4), (3, 200)):
+        r = torch.randn(P * n, generator=g, device="cuda") * 3 + 1
+        r[:n] = 2.5                                           # one constant group
+        for norm in (False, True):
+            got = lib.group_advantages(r, n, normalise_std=norm, eps=1e-6)
+            ref = orc.group_advantages(f64(r), n, normalise_std=norm, eps=1e-6)
+            assert np.abs(f64(got) - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())
+            assert not bool(got[:n].any())

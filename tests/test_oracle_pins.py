@@ -441,3 +441,26 @@ def test_ppo_mode_matches_torch_autograd_and_has_zero_gradient_outside_bounds(ep
     assert dead.any() and not out["coef"][dead].any()
     live = ~dead & (mask.reshape(-1) != 0)
     assert np.all(out["coef"][live] != 0)
+
+
+# ---------------------------------------------------------------- group-mean baseline (Sec. 6)
+def test_group_advantages_closed_forms_and_loop():
+    # hand example: rewards (1, 0, 0, 1 | 3, 3, 3, 3 | 2, 0, 0, 0), n = 4
+    r = np.array([1, 0, 0, 1, 3, 3, 3, 3, 2, 0, 0, 0], dtype=np.float64)
+    a = orc.group_advantages(r, 4)
+    assert np.allclose(a, [0.5, -0.5, -0.5, 0.5, 0, 0, 0, 0, 1.5, -0.5, -0.5, -0.5], rtol=0, atol=1e-15)
+    # normalised: group 0 has population std 1/2 -> +-1; a constant group stays 0 (eps keeps it finite)
+    b = orc.group_advantages(r, 4, normalise_std=True, eps=1e-9)
+    assert np.allclose(b[:4], [1, -1, -1, 1], rtol=1e-8) and np.all(b[4:8] == 0)
+    assert np.allclose(b[8:], np.array([1.5, -0.5, -0.5, -0.5]) / math.sqrt(0.75), rtol=1e-8)
+    # against a plain loop on random rewards; every group sums to zero
+    rng = np.random.default_rng(3)
+    r = rng.standard_normal(7 * 5)
+    a = orc.group_advantages(r, 5)
+    for p in range(7):
+        g = r[5 * p:5 * p + 5]
+        m = sum(g) / 5
+        assert np.allclose(a[5 * p:5 * p + 5], [x - m for x in g], rtol=0, atol=1e-15)
+        assert abs(a[5 * p:5 * p + 5].sum()) < 1e-14
+    c = orc.group_advantages(r, 5, normalise_std=True, eps=0.0).reshape(7, 5)
+    assert np.allclose((c * c).mean(axis=1), 1.0, rtol=1e-12)
