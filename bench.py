@@ -62,6 +62,36 @@ def measured_traffic(kernel):
     return None
 
 
+class HipEvents:
+    """Raw HIP events through the runtime torch already loaded: the backward's phase boundaries are recorded by
+    the library itself (llamarl_offpolicy_loss_bwd_phases), which needs hipEvent_t handles."""
+
+    def __init__(self):
+        import ctypes
+        self.ct = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self, n):
+        out = []
+        for _ in range(n):
+            e = self.ct.c_void_p()
+            assert self.hip.hipEventCreate(self.ct.byref(e)) == 0
+            out.append(e.value)
+        return out
+
+    def elapsed_ms(self, a, b):
+        ms = self.ct.c_float()
+        assert self.hip.hipEventElapsedTime(self.ct.byref(ms), self.ct.c_void_p(a), self.ct.c_void_p(b)) == 0
+        return float(ms.value)
+
+    def destroy(self, evs):
+        for e in evs:
+            self.hip.hipEventDestroy(self.ct.c_void_p(e))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,8 +138,10 @@ def main():
     stream = torch.cuda.current_stream()
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    hipev = HipEvents()
+    phase = [hipev.create(6) for _ in range(args.steps)]      # backward phase boundaries, recorded by the library
 
-    def step(e=None):
+    def step(e=None, ph=None):
         if e:
             e[0].record(stream)
         logp, lse = L.token_logprobs(x["H"], x["W"], x["targets"], mask_flat, ws=ws_fwd, stream=stream)
@@ -119,7 +151,8 @@ def main():
                                                  targets=x["targets"], V=V, ws=ws_loss, stream=stream)
         if e:
             e[2].record(stream)
-        L.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef, dH=dH, dW=dW, ws=ws_bwd, stream=stream)
+        L.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef, dH=dH, dW=dW, ws=ws_bwd, stream=stream,
+                             phase_events=ph)
         if e:
             e[3].record(stream)
         return loss, stats
@@ -129,7 +162,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        loss, stats = step(ev[k])
+        loss, stats = step(ev[k], phase[k])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
@@ -141,6 +174,21 @@ def main():
     # 2 * n_valid * V * d flop (never the 2 * N * V * d of the padded batch).
     flops_gemm = 2.0 * n_valid * V * d
     fwd_tflops = flops_gemm / (t_lp * 1e-3) / 1e12
+    t_dz = sum(hipev.elapsed_ms(p[1], p[2]) for p in phase) / args.steps      # k_bwd_dz alone
+    t_dh = sum(hipev.elapsed_ms(p[2], p[3]) for p in phase) / args.steps      # dH contraction alone
+    t_dw = sum(hipev.elapsed_ms(p[4], p[5]) for p in phase) / args.steps      # dW contraction alone
+    for p in phase:
+        hipev.destroy(p)
+    kernels = [
+        ("k_fwd_partials (LM-head contraction + online logsumexp; timed as llamarl_token_logprobs, i.e. with "
+         "~0.1 ms of row compaction and partial merge)", t_lp),
+        ("k_bwd_dz (logits recompute + dz)", t_dz),
+        ("k_gemm_store<k-major> (dH = dz W, split-K partials)" if w.dtype == "bf16" else "k_gemm_store (dH)", t_dh),
+        ("k_gemm_store (dW = dz^T H)", t_dw),
+    ]
+    per_kernel = [{"kernel": n, "ms": t, "achieved": flops_gemm / (t * 1e-3) / 1e12, "unit": "TFLOP/s",
+                   "frac": flops_gemm / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS} for n, t in kernels]
+    dom = max(per_kernel, key=lambda k: k["ms"])                             # the dominant (slowest) contraction
     out = {
         "metric": METRIC, "value": N / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
@@ -152,14 +200,15 @@ def main():
         "mfma_peak_frac_model_6NVd": 3 * flops_gemm / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "ms_token_logprobs": t_lp, "ms_loss_fwd": t_loss, "ms_loss_bwd": t_bwd,
         "loss": float(loss.item()), "stats": [float(v) for v in stats.tolist()],
-        "roofline": {"bound": "mfma", "kernel": "k_fwd_partials<BF16> (LM-head contraction + online logsumexp), "
-                     "timed as llamarl_token_logprobs; 2*n_valid*V*d flop per launch",
-                     "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": fwd_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic("k_fwd_partials") if w.name == "llama3_8b" else None,
-                     "traffic_note": "bytes per launch, rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0 (plain-copy "
-                                     "calibration); algorithmic bytes are W + active H rows = %.3g" %
-                                     ((V * d + n_valid * d) * (2 if w.dtype == "bf16" else 4))},
+        # the dominant kernel = the slowest of the four contractions, each 2*n_valid*V*d flop per launch
+        "roofline": {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["achieved"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"],
+                     "traffic": measured_traffic(dom["kernel"].split()[0].split("<")[0] +
+                                                 ("<llamarl::BF16, true" if "k-major" in dom["kernel"] else ""))
+                     if w.name == "llama3_8b" else None,
+                     "traffic_note": "bytes per launch between L2 and fabric, rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE "
+                                     "x1.0 (plain-copy calibration; includes Infinity-Cache hits)"},
+        "roofline_per_kernel": per_kernel,
     }
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(x, w, args.cpu_rows)

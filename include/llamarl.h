@@ -160,6 +160,20 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Measurement aid: llamarl_offpolicy_loss_bwd, which in addition records six caller-owned HIP events
+ * (phase_events[0..5], HOST array of hipEvent_t passed as void*) on `stream`: [0] before the first kernel,
+ * [1] after the set-up kernels (active-row list, zeroed dH rows, operand panels), [2] after the recompute + dz
+ * kernel, [3] after the dH contraction, [4] after its split reduction, [5] after the dW contraction.  Same results, same
+ * kernels, same error behaviour (plus INVALID_ARG for a null event).  The backward's four stages are all in this
+ * one call, so per-kernel rooflines of the backward can only be timed from inside it.
+ */
+llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, const int32_t* targets,
+                                                 const float* lse, const float* coef, float grad_loss, int64_t N,
+                                                 int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
+                                                 llamarl_dtype dW_dt, int accumulate_dW, void* ws, size_t ws_bytes,
+                                                 void* stream, void* const* phase_events);
+
+/*
  * Group-mean baseline (Sec. 6: from one prompt, n generations are sampled and the baseline is the mean of their
  * rewards, constant over the tokens of a generation):
  *     adv[p,i] = r[p,i] - (1/n) sum_j r[p,j]

@@ -20,7 +20,8 @@ NORM_TOKEN_MEAN, NORM_SEQ_MEAN, NORM_SUM_T_MEAN_B = 0, 1, 2
 PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
-           "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_group_advantages")
+           "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
+           "llamarl_group_advantages")
 
 
 class LlamarlError(RuntimeError):
@@ -59,6 +60,9 @@ def load():
                                                vp, vp, vp, vp, sz, vp]
     lib.llamarl_offpolicy_loss_bwd.restype = ci
     lib.llamarl_offpolicy_loss_bwd.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, ci, vp, vp, ci, ci, vp, sz, vp]
+    lib.llamarl_offpolicy_loss_bwd_phases.restype = ci
+    lib.llamarl_offpolicy_loss_bwd_phases.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, ci, vp, vp, ci, ci, vp, sz,
+                                                      vp, ctypes.POINTER(vp)]
     lib.llamarl_group_advantages.restype = ci
     lib.llamarl_group_advantages.argtypes = [vp, i64, i64, ci, cf, vp, vp]
     _lib = lib
@@ -152,8 +156,9 @@ def offpolicy_loss_fwd(logp, mu_logp, adv, mask, B, T, rho=2.0, norm_mode=NORM_T
 
 
 def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0, dW_dtype=None, dW=None, accumulate_dW=False,
-                       dH=None, ws=None, stream=None):
-    """llamarl_offpolicy_loss_bwd: returns (dH [N,d] in H's dtype, dW [V,d] in dW_dtype)."""
+                       dH=None, ws=None, stream=None, phase_events=None):
+    """llamarl_offpolicy_loss_bwd: returns (dH [N,d] in H's dtype, dW [V,d] in dW_dtype).
+    phase_events: six raw hipEvent_t handles (ints) -> llamarl_offpolicy_loss_bwd_phases is called instead."""
     lib = load()
     dt = _dtype_code(H)
     _need(H, H.dtype, "H"); _need(W, H.dtype, "W"); _need(targets, torch.int32, "targets")
@@ -172,9 +177,13 @@ def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0, dW_dtype=None, d
         dH = torch.empty(N, d, dtype=H.dtype, device=H.device)
     _need(dW, dW_dtype, "dW"); _need(dH, H.dtype, "dH")
     ws = _workspace(workspace_bytes(N, d, V, dt, PASS_LOSS_BWD), H.device, ws)
-    _check(lib.llamarl_offpolicy_loss_bwd(_ptr(H), _ptr(W), _ptr(targets), _ptr(lse), _ptr(coef), float(grad_loss),
-                                          N, d, V, dt, _ptr(dH), _ptr(dW), _dtype_code(dW), int(bool(accumulate_dW)),
-                                          _ptr(ws), ws.numel(), _stream(stream)))
+    args = (_ptr(H), _ptr(W), _ptr(targets), _ptr(lse), _ptr(coef), float(grad_loss), N, d, V, dt, _ptr(dH), _ptr(dW),
+            _dtype_code(dW), int(bool(accumulate_dW)), _ptr(ws), ws.numel(), _stream(stream))
+    if phase_events is None:
+        _check(lib.llamarl_offpolicy_loss_bwd(*args))
+    else:
+        ev = (ctypes.c_void_p * 6)(*[ctypes.c_void_p(int(e)) for e in phase_events])
+        _check(lib.llamarl_offpolicy_loss_bwd_phases(*args, ev))
     return dH, dW
 
 

@@ -86,10 +86,11 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
   w.off_nact = w.off_rows + (size_t)round_up(w.ldzt * (int64_t)sizeof(int32_t), 256);
   w.off_part = w.off_nact + 256;
   // dH has few output tiles (N/256 x d/256) with a very long K = V: split K until there are enough work items
-  // to fill 256 CUs evenly whatever the number of active rows turns out to be.  d % 4 keeps float4 rows.
+  // to fill 256 CUs evenly (at most ~1/16 of the last round idle) whatever the number of active rows turns out to
+  // be.  d % 4 keeps float4 rows.
   const int64_t tiles = ((N + BM - 1) / BM) * ((d + BN - 1) / BN);
   int s = 1;
-  while (s < 8 && tiles * s < 4096 && (w.ldz / 64) / (s * 2) >= 16) s *= 2;
+  while (s < 8 && tiles * s < 8192 && (w.ldz / 64) / (s * 2) >= 16) s *= 2;
   w.dh_splits = s;
   w.total = w.off_part + (s > 1 ? (size_t)round_up((int64_t)s * N * d * 4, 256) : 0);
   return w;
@@ -201,9 +202,13 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
 template <typename TT>
 llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, const float* lse, const float* coef,
                        float g, int64_t N, int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
-                       llamarl_dtype dW_dt, int accumulate_dW, char* ws, hipStream_t st) {
+                       llamarl_dtype dW_dt, int accumulate_dW, char* ws, hipStream_t st, void* const* ev) {
   typedef typename TT::store_t stt;
   const BwdWs w = bwd_ws(N, d, V, dt);
+  // ev (optional, 6 caller-owned hipEvent_t): recorded on the stream at the phase boundaries
+#define PHASE_EVENT(i) \
+  do { if (ev) HIP_TRY(hipEventRecord(reinterpret_cast<hipEvent_t>(ev[i]), st)); } while (0)
+  PHASE_EVENT(0);
   stt* dz = reinterpret_cast<stt*>(ws + w.off_dz);
   stt* dzt = reinterpret_cast<stt*>(ws + w.off_dzt);
   stt* wt = reinterpret_cast<stt*>(ws + w.off_wt);
@@ -228,6 +233,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
       reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, rows, n_act);
   HIP_TRY(hipGetLastError());
 
+  PHASE_EVENT(1);
   // recompute logits tile by tile, turn them into dz (rows / columns = list positions)
   DzArgs a;
   a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
@@ -239,6 +245,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
   HIP_TRY(hipGetLastError());
 
+  PHASE_EVENT(2);
   // dH [active rows, d] = dz [n_act,V] . W [V,d], scattered to the token rows.
   //   bf16: k-major operands dz^T [V][n_act] and W [V][d], K = V exactly
   //   fp32: K-contiguous operands dz [n_act][ldz] and W^T [d][ldz], K zero-padded to ldz
@@ -255,14 +262,20 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
                               w.dh_splits, N * d, st);
   }
   if (s != LLAMARL_OK) return s;
+  PHASE_EVENT(3);
   if (w.dh_splits > 1) {
     k_reduce_splits<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(part, w.dh_splits, N * d, rows, n_act, d,
                                                                  reinterpret_cast<stt*>(dH), d);
     HIP_TRY(hipGetLastError());
   }
+  PHASE_EVENT(4);
   // dW [V,d] = dz^T [V,n_act] . H^T[d,n_act]^T          (K = n_act, zero-padded to a multiple of 64)
-  return launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW,
-                               nullptr, n_act, nullptr, 1, 0, st);
+  s = launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW, nullptr,
+                            n_act, nullptr, 1, 0, st);
+  if (s != LLAMARL_OK) return s;
+  PHASE_EVENT(5);
+#undef PHASE_EVENT
+  return LLAMARL_OK;
 }
 
 }  // namespace
@@ -346,10 +359,10 @@ llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_log
   return LLAMARL_OK;
 }
 
-llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const int32_t* targets, const float* lse,
-                                          const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
-                                          llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
-                                          int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
+static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* targets, const float* lse,
+                                const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
+                                llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt, int accumulate_dW,
+                                void* ws, size_t ws_bytes, void* stream, void* const* ev) {
   if (!H || !W || !targets || !lse || !coef || !dH || !dW) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
   llamarl_status s = check_head_shape(N, d, V, dt);
   if (s != LLAMARL_OK) return s;
@@ -365,9 +378,29 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (dt == LLAMARL_BF16)
     return run_bwd<BF16>(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW,
-                         reinterpret_cast<char*>(ws), st);
+                         reinterpret_cast<char*>(ws), st, ev);
   return run_bwd<F32>(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW,
-                      reinterpret_cast<char*>(ws), st);
+                      reinterpret_cast<char*>(ws), st, ev);
+}
+
+llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const int32_t* targets, const float* lse,
+                                          const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
+                                          llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
+                                          int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes, stream,
+                   nullptr);
+}
+
+llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, const int32_t* targets,
+                                                 const float* lse, const float* coef, float grad_loss, int64_t N,
+                                                 int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
+                                                 llamarl_dtype dW_dt, int accumulate_dW, void* ws, size_t ws_bytes,
+                                                 void* stream, void* const* phase_events) {
+  if (!phase_events) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events is null");
+  for (int i = 0; i < 6; ++i)
+    if (!phase_events[i]) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events[%d] is null", i);
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes, stream,
+                   phase_events);
 }
 
 llamarl_status llamarl_group_advantages(const float* rewards, int64_t P, int64_t n, int normalise_std, float eps,

@@ -168,3 +168,27 @@ def test_group_advantages(lib):
             ref = orc.group_advantages(f64(r), n, normalise_std=norm, eps=1e-6)
             assert np.abs(f64(got) - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())
             assert not bool(got[:n].any())
+
+
+def test_phase_event_variant_of_the_backward_gives_the_same_bits(lib):
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    evs = []
+    for _ in range(6):
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        evs.append(e.value)
+    w = synth.scaled(W8, d=256, V=1000, B=2, T=300, len_lo=50, len_hi=300)
+    x = synth.make_inputs(w, "cuda")
+    a = run_hip(lib, x)
+    dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], a["lse"], a["coef"], phase_events=evs)
+    torch.cuda.synchronize()
+    assert torch.equal(dH, a["dH"]) and torch.equal(dW, a["dW"])
+    ms = ctypes.c_float()
+    for i in range(5):
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(evs[i]), ctypes.c_void_p(evs[i + 1])) == 0
+        assert ms.value >= 0.0
+    for e in evs:
+        hip.hipEventDestroy(ctypes.c_void_p(e))
