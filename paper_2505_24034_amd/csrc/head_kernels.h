@@ -6,7 +6,8 @@
 //   k_bwd_dz         recomputed logits tile -> dz = g * coef * (onehot - softmax), written in both orientations
 //   k_gemm_store     plain contraction with a store epilogue: dW = dz^T H (K-contiguous operands) and
 //                    dH = dz W (k-major operands: dz^T as written, W as the caller holds it; bf16)
-//   k_transpose      [R,C] -> [C,R] with zero padding (W^T and H^T panels for the two backward contractions)
+//   k_transpose      [R,C] -> [C,R] with zero padding and row gather (H^T panel of the active tokens; fp32: W^T too)
+//   k_compact_rows   ascending list of active token rows; k_zero_inactive_rows, k_reduce_splits: small helpers
 //
 // In the two logits kernels the MFMA "row" operand is W (vocab) and the "column" operand is H (tokens): an
 // accumulator lane then holds ONE token (column = lane % 32) and 16 vocab entries per 32x32 block, so the
