@@ -233,6 +233,19 @@ def group_advantages(rewards, n, normalise_std=False, eps=1e-6):
     return a.reshape(-1)
 
 
+def kl_shaped_rewards(rewards, logp, base_logp, mask, lambda_kl):
+    """KL-regularised reward (Sec. 6: the single reward per generation is combined with
+    lambda_KL * D_KL(pi(y|x), pi_base(y|x)) to penalise deviation from the reference policy).  The paper gives
+    no estimator; the reading taken: the sequence KL is E_{y~pi} sum_t [log pi(y_t|.) - log pi_base(y_t|.)], so
+    the estimate on one sampled generation is the masked sum of the per-token log-ratios, and the penalty is
+    subtracted:  kl_b = sum_t mask (logp - base_logp),  shaped_b = r_b - lambda_KL kl_b.
+    logp, base_logp, mask: [B,T]; rewards: [B].  Returns (shaped [B], kl [B])."""
+    m = np.asarray(mask).astype(bool)
+    lr = np.where(m, np.asarray(logp, dtype=np.float64) - np.asarray(base_logp, dtype=np.float64), 0.0)
+    kl = lr.sum(axis=1)
+    return np.asarray(rewards, dtype=np.float64) - float(lambda_kl) * kl, kl
+
+
 def aipo_step(H, W, targets, mu_logp, adv, mask, rho, norm_mode=NORM_TOKEN_MEAN, grad_loss=1.0,
               clip_mode=CLIP_AIPO, eps_lo=0.2, eps_hi=0.2):
     """The whole path in order: log-probs, loss, gradients."""

@@ -464,3 +464,52 @@ def test_group_advantages_closed_forms_and_loop():
         assert abs(a[5 * p:5 * p + 5].sum()) < 1e-14
     c = orc.group_advantages(r, 5, normalise_std=True, eps=0.0).reshape(7, 5)
     assert np.allclose((c * c).mean(axis=1), 1.0, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- KL-regularised reward (Sec. 6)
+def test_kl_shaped_rewards_expectation_is_the_exact_sequence_kl():
+    # Enumerate every sequence of a T=3, V=3 model with position-wise independent categoricals: under y ~ pi the
+    # mean of the per-sequence estimate must be the exact KL(pi || base) = sum of the per-position KLs (scipy's
+    # rel_entr), and the mean shaped reward E[r] - lambda * KL.  KL is not symmetric: swapped arguments fail.
+    from itertools import product
+    from scipy.special import rel_entr
+    rng = np.random.default_rng(11)
+    T, V, lam = 3, 3, 0.37
+    pi = rng.dirichlet(np.ones(V), size=T)
+    base = rng.dirichlet(np.ones(V), size=T)
+    seqs = np.array(list(product(range(V), repeat=T)))                    # [27, T]
+    logp = np.log(pi)[np.arange(T)[None, :], seqs]
+    base_logp = np.log(base)[np.arange(T)[None, :], seqs]
+    prob = np.exp(logp.sum(axis=1))
+    assert abs(prob.sum() - 1.0) < 1e-14
+    rewards = rng.standard_normal(len(seqs))
+    shaped, kl = orc.kl_shaped_rewards(rewards, logp, base_logp, np.ones_like(seqs, dtype=np.uint8), lam)
+    exact = rel_entr(pi, base).sum()
+    assert abs((prob * kl).sum() - exact) < 1e-13
+    assert abs((prob * shaped).sum() - ((prob * rewards).sum() - lam * exact)) < 1e-13
+    assert abs((prob * kl).sum() - rel_entr(base, pi).sum()) > 1e-3
+
+
+def test_kl_shaped_rewards_special_cases():
+    rng = np.random.default_rng(12)
+    B, T = 4, 9
+    logp = -rng.random((B, T)) * 3
+    base = -rng.random((B, T)) * 3
+    mask = (rng.random((B, T)) < 0.6).astype(np.uint8)
+    mask[2] = 0                                                           # an empty generation
+    r = rng.standard_normal(B)
+    # lambda = 0 and pi = base leave the reward alone
+    assert np.array_equal(orc.kl_shaped_rewards(r, logp, base, mask, 0.0)[0], r)
+    s, kl = orc.kl_shaped_rewards(r, logp, logp, mask, 5.0)
+    assert np.array_equal(s, r) and np.all(kl == 0)
+    # masked positions never count (NaN there is ignored); plain loops give the same numbers
+    dirty = logp.copy()
+    dirty[mask == 0] = np.nan
+    s, kl = orc.kl_shaped_rewards(r, dirty, base, mask, 0.5)
+    for b in range(B):
+        k = sum(logp[b, t] - base[b, t] for t in range(T) if mask[b, t])
+        assert abs(kl[b] - k) < 1e-14 and abs(s[b] - (r[b] - 0.5 * k)) < 1e-14
+    assert kl[2] == 0 and s[2] == r[2]
+    # a policy more confident than the base on its own samples is penalised (sign of the term)
+    s, kl = orc.kl_shaped_rewards(np.zeros(1), np.full((1, 4), -0.1), np.full((1, 4), -2.0), np.ones((1, 4)), 1.0)
+    assert kl[0] > 0 and s[0] < 0
