@@ -187,6 +187,25 @@ llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, c
 llamarl_status llamarl_group_advantages(const float* rewards, int64_t P, int64_t n, int normalise_std, float eps,
                                         float* adv, void* stream);
 
+/*
+ * KL-regularised reward (Sec. 6: the reward of a generation is often combined with
+ * lambda_KL * D_KL(pi(y|x), pi_base(y|x)) to penalise deviation from the reference policy).  The paper gives no
+ * estimator; this one is the sampled-token estimate of the sequence KL, subtracted from the reward:
+ *     kl[b]     = sum_t mask[b,t] * (logp[b,t] - base_logp[b,t])
+ *     shaped[b] = rewards[b] - lambda_kl * kl[b]
+ * base_logp is what a second llamarl_token_logprobs call returns with the reference model's hidden states and
+ * head; `shaped` then feeds llamarl_group_advantages.
+ *
+ *   rewards         in  float [B]
+ *   logp, base_logp in  float [B*T]
+ *   mask            in  uint8 [B*T] or NULL (= all valid); masking is a select (NaN at masked rows is ignored)
+ *   shaped          out float [B]  (may alias rewards)
+ *   kl              out float [B] or NULL
+ */
+llamarl_status llamarl_kl_shaped_rewards(const float* rewards, const float* logp, const float* base_logp,
+                                         const uint8_t* mask, int64_t B, int64_t T, float lambda_kl, float* shaped,
+                                         float* kl, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

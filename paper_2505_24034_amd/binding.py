@@ -21,7 +21,7 @@ PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
            "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
-           "llamarl_group_advantages")
+           "llamarl_group_advantages", "llamarl_kl_shaped_rewards")
 
 
 class LlamarlError(RuntimeError):
@@ -65,6 +65,8 @@ def load():
                                                       vp, ctypes.POINTER(vp)]
     lib.llamarl_group_advantages.restype = ci
     lib.llamarl_group_advantages.argtypes = [vp, i64, i64, ci, cf, vp, vp]
+    lib.llamarl_kl_shaped_rewards.restype = ci
+    lib.llamarl_kl_shaped_rewards.argtypes = [vp, vp, vp, vp, i64, i64, cf, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -198,3 +200,23 @@ def group_advantages(rewards, n, normalise_std=False, eps=1e-6, stream=None):
     _check(lib.llamarl_group_advantages(_ptr(rewards), P, n, int(bool(normalise_std)), float(eps), _ptr(adv),
                                         _stream(stream)))
     return adv
+
+
+def kl_shaped_rewards(rewards, logp, base_logp, mask, lambda_kl, stream=None):
+    """llamarl_kl_shaped_rewards: rewards [B], logp / base_logp / mask [B,T] -> (shaped [B], kl [B])."""
+    lib = load()
+    _need(rewards, torch.float32, "rewards")
+    _need(logp, torch.float32, "logp")
+    _need(base_logp, torch.float32, "base_logp")
+    if mask is not None:
+        _need(mask, torch.uint8, "mask")
+    B = rewards.numel()
+    if B <= 0 or logp.numel() % B != 0 or base_logp.numel() != logp.numel() or \
+            (mask is not None and mask.numel() != logp.numel()):
+        raise LlamarlError(ERR_INVALID_ARG, "logp, base_logp and mask must hold B*T entries")
+    T = logp.numel() // B
+    shaped = torch.empty_like(rewards)
+    kl = torch.empty_like(rewards)
+    _check(lib.llamarl_kl_shaped_rewards(_ptr(rewards), _ptr(logp), _ptr(base_logp), _ptr(mask), B, T,
+                                         float(lambda_kl), _ptr(shaped), _ptr(kl), _stream(stream)))
+    return shaped, kl

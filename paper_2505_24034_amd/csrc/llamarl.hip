@@ -415,4 +415,17 @@ llamarl_status llamarl_group_advantages(const float* rewards, int64_t P, int64_t
   return LLAMARL_OK;
 }
 
+llamarl_status llamarl_kl_shaped_rewards(const float* rewards, const float* logp, const float* base_logp,
+                                         const uint8_t* mask, int64_t B, int64_t T, float lambda_kl, float* shaped,
+                                         float* kl, void* stream) {
+  if (!rewards || !logp || !base_logp || !shaped) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  if (B <= 0 || T <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "B and T must be positive");
+  if (B >= (int64_t)1 << 31) return fail(LLAMARL_ERR_UNSUPPORTED, "too many generations");
+  if (!(lambda_kl == lambda_kl)) return fail(LLAMARL_ERR_INVALID_ARG, "lambda_kl is NaN");
+  k_kl_shaped_rewards<<<dim3((unsigned)B), dim3(LOSS_THREADS), 0, reinterpret_cast<hipStream_t>(stream)>>>(
+      rewards, logp, base_logp, mask, T, lambda_kl, shaped, kl);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
 }  // extern "C"

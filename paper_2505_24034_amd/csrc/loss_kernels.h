@@ -216,4 +216,29 @@ __global__ __launch_bounds__(256) void k_group_advantages(const float* rewards, 
   for (int64_t i = lane; i < n; i += 64) adv[p * n + i] = (float)(((double)r[i] - mean) * scale);
 }
 
+// One block per generation: masked sum of the per-token log-ratios log pi - log pi_base (fp64, fixed order), then
+// shaped = reward - lambda * sum.  Masking is a select, so NaN at masked positions never enters the sum.
+__global__ __launch_bounds__(LOSS_THREADS) void k_kl_shaped_rewards(const float* rewards, const float* logp,
+                                                                    const float* base_logp, const uint8_t* mask,
+                                                                    int64_t T, float lambda_kl, float* shaped,
+                                                                    float* kl) {
+  __shared__ double s_w[LOSS_THREADS / 64];
+  const int64_t b = blockIdx.x;
+  double acc = 0.0;
+  for (int64_t t = threadIdx.x; t < T; t += LOSS_THREADS) {
+    const int64_t i = b * T + t;
+    const bool m = (mask == nullptr) || (mask[i] != 0);
+    acc += m ? ((double)logp[i] - (double)base_logp[i]) : 0.0;
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double k = 0.0;
+    for (int w = 0; w < LOSS_THREADS / 64; ++w) k += s_w[w];
+    if (kl != nullptr) kl[b] = (float)k;
+    shaped[b] = (float)((double)rewards[b] - (double)lambda_kl * k);
+  }
+}
+
 }  // namespace llamarl

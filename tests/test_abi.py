@@ -113,6 +113,16 @@ def test_group_advantages_rejects_bad_arguments(clib):
     assert clib.llamarl_group_advantages(vp(1 << 20), 2, 2, 1, -1.0, vp(1 << 21), None) == binding.ERR_INVALID_ARG
 
 
+@no_gpu_only
+def test_kl_shaped_rewards_rejects_bad_arguments(clib):
+    vp = ctypes.c_void_p
+    a, b, c, o = vp(1 << 20), vp(1 << 21), vp(1 << 22), vp(1 << 23)
+    assert clib.llamarl_kl_shaped_rewards(None, b, c, None, 2, 2, 0.1, o, None, None) == binding.ERR_INVALID_ARG
+    assert clib.llamarl_kl_shaped_rewards(a, b, c, None, 2, 2, 0.1, None, None, None) == binding.ERR_INVALID_ARG
+    assert clib.llamarl_kl_shaped_rewards(a, b, c, None, 0, 2, 0.1, o, None, None) == binding.ERR_INVALID_ARG
+    assert clib.llamarl_kl_shaped_rewards(a, b, c, None, 2, 2, float("nan"), o, None, None) == binding.ERR_INVALID_ARG
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libllamarl.so")

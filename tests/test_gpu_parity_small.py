@@ -172,6 +172,46 @@ def test_group_advantages(lib):
             assert not bool(got[:n].any())
 
 
+def test_kl_shaped_rewards_from_two_logprob_calls(lib):
+    # the reference policy's log-probs come from a second llamarl_token_logprobs call with another head
+    from oracle import aipo_oracle as orc
+    w = synth.scaled(W8, d=256, V=1500, B=6, T=200, len_lo=0, len_hi=200, seed=31)
+    inp = synth.make_inputs(w, "cuda")
+    B, T = w.B, w.T
+    g = torch.Generator(device="cuda").manual_seed(32)
+    W_base = (inp["W"].float() + 0.05 * torch.randn(inp["W"].shape, generator=g, device="cuda")).to(inp["W"].dtype)
+    rewards = torch.randn(B, generator=g, device="cuda")
+    mask = inp["mask"].reshape(-1)
+    logp, _ = lib.token_logprobs(inp["H"], inp["W"], inp["targets"], mask)
+    base_logp, _ = lib.token_logprobs(inp["H"], W_base, inp["targets"], mask)
+    o = {k: synth.to_oracle(inp[k]) for k in ("H", "W", "targets", "mask")}
+    ref_logp, _ = orc.token_logprobs(o["H"], o["W"], o["targets"], o["mask"].reshape(-1))
+    ref_base, _ = orc.token_logprobs(o["H"], synth.to_oracle(W_base), o["targets"], o["mask"].reshape(-1))
+    for lam in (0.0, 0.05, 1.0):
+        shaped, kl = lib.kl_shaped_rewards(rewards, logp, base_logp, mask, lam)
+        # the kernel alone, on the very log-probs it read: fp32 inputs, fp64 sum -> rounding of the output only
+        rs, rk = orc.kl_shaped_rewards(f64(rewards), f64(logp).reshape(B, T), f64(base_logp).reshape(B, T),
+                                       o["mask"].reshape(B, T), lam)
+        assert np.abs(f64(kl) - rk).max() <= 1e-6 * max(1.0, np.abs(rk).max())
+        assert np.abs(f64(shaped) - rs).max() <= 1e-6 * max(1.0, np.abs(rs).max())
+        # the chain against the oracle chain: bf16 log-prob tolerance times the tokens summed
+        cs, ck = orc.kl_shaped_rewards(f64(rewards), ref_logp.reshape(B, T), ref_base.reshape(B, T),
+                                       o["mask"].reshape(B, T), lam)
+        n_tok = o["mask"].reshape(B, T).sum(axis=1)
+        assert np.all(np.abs(f64(kl) - ck) <= 2 * 2e-2 * np.maximum(n_tok, 1))
+        assert np.all(np.abs(f64(shaped) - cs) <= lam * 2 * 2e-2 * np.maximum(n_tok, 1) + 1e-6)
+    # NaN at masked positions is ignored; a null mask counts every position
+    dirty = logp.clone()
+    dirty[mask == 0] = float("nan")
+    s2, k2 = lib.kl_shaped_rewards(rewards, dirty, base_logp, mask, 0.05)
+    s1, k1 = lib.kl_shaped_rewards(rewards, logp, base_logp, mask, 0.05)
+    assert torch.equal(s1, s2) and torch.equal(k1, k2)
+    s3, k3 = lib.kl_shaped_rewards(rewards, logp, base_logp, None, 0.05)
+    rs, rk = orc.kl_shaped_rewards(f64(rewards), f64(logp).reshape(B, T), f64(base_logp).reshape(B, T),
+                                   np.ones((B, T)), 0.05)
+    assert np.abs(f64(k3) - rk).max() <= 1e-6 * max(1.0, np.abs(rk).max())
+
+
 def test_phase_event_variant_of_the_backward_gives_the_same_bits(lib):
     import ctypes
     hip = ctypes.CDLL("libamdhip64.so")
