@@ -86,7 +86,20 @@ struct LanePos {
     return wm * WAVE_M + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
   }
   __device__ __forceinline__ int col(int j) const { return wn * WAVE_N + j * 32 + (lane & 31); }
+  // Pair-interleaved columns (see paired_row): the lane's two column blocks hold NEIGHBOURING columns, so a lane
+  // owns a contiguous pair and 32 lanes own 64 consecutive columns of one row.
+  __device__ __forceinline__ int col_pair() const { return wn * WAVE_N + 2 * (lane & 31); }
 };
+
+// Which row of an operand tile the loader puts into LDS row `r`.  A wave's 64 LDS rows of the column operand feed
+// its two 32-column MFMA blocks (block j = bit 5, MFMA column n = low 5 bits); with pairing, block j / column n is
+// tile row 2n + j of those 64, so that accumulator registers acc[.][0] and acc[.][1] of a lane are neighbouring
+// output columns.  Only the global side changes: LDS layout, swizzle and fragment reads stay as they are.
+template <bool PAIR>
+__device__ __forceinline__ int tile_row_of(int r) {
+  static_assert(TN == 2 && WAVE_N == 64, "pairing interleaves exactly two column blocks");
+  return PAIR ? ((r & ~63) | ((r & 31) << 1) | ((r >> 5) & 1)) : r;
+}
 
 // Persistent tile schedule.  The grid has one workgroup per CU (any size works); workgroups are dealt round-robin
 // to the 8 XCDs, each with a private L2.  Every XCD owns a contiguous run of tile ids and its workgroups walk it
@@ -154,18 +167,20 @@ struct SlabLoader {
     return (lane & 7) ^ swizzle(wave * 8 + (lane >> 3));
   }
   // base: first row of the tile; ld in elements; rows_valid <= 256 rows exist from base on.
+  template <bool PAIR = false>
   __device__ __forceinline__ void init(const void* base, int64_t ld, int rows_valid, int wave, int lane) {
     const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
     set_base(base, row_bytes * (uint32_t)rows_valid);
     const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = (it * 8 + wave) * 8 + (lane >> 3);
+      const int row = tile_row_of<PAIR>((it * 8 + wave) * 8 + (lane >> 3));
       voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + c16 : OOB_OFFSET;
     }
   }
   // Gathered panel: tile row r is row rows[r] of the whole matrix `base` (total_rows rows, < 2^31 bytes).
   // Free with per-lane buffer offsets: this is how masked tokens are skipped without a packed copy of H.
+  template <bool PAIR = false>
   __device__ __forceinline__ void init_gather(const void* base, int64_t ld, int64_t total_rows, const int32_t* rows,
                                               int rows_valid, int wave, int lane) {
     const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
@@ -173,7 +188,7 @@ struct SlabLoader {
     const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = (it * 8 + wave) * 8 + (lane >> 3);
+      const int row = tile_row_of<PAIR>((it * 8 + wave) * 8 + (lane >> 3));
       voff[it] = (row < rows_valid) ? (uint32_t)rows[row] * row_bytes + c16 : OOB_OFFSET;
     }
   }
@@ -243,7 +258,8 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
 //   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1
 //
 // GATHER_B: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
-// tile row r is its row b_rows[r].
+// tile row r is its row b_rows[r].  PAIR_B: output columns are pair-interleaved over the lane's two column blocks
+// (tile_row_of); the epilogue must then take its columns from LanePos::col_pair().
 template <typename TT>
 struct TileGemm {
   typedef typename TT::frag_t frag_t;
@@ -251,15 +267,15 @@ struct TileGemm {
   SlabLoader<TT> la, lb;
   int K;
 
-  template <bool GATHER_B>
+  template <bool GATHER_B, bool PAIR_B = false>
   __device__ __forceinline__ void prefetch(const void* A_tile, int64_t lda, int rowsA, const void* B_tile, int64_t ldb,
                                            int rowsB, int64_t K_, char* smem, const int32_t* b_rows = nullptr,
                                            int64_t b_total = 0) {
     const int lane = threadIdx.x & 63, wave = wave_id();
     K = (int)K_;
     la.init(A_tile, lda, rowsA, wave, lane);
-    if constexpr (GATHER_B) lb.init_gather(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
-    else lb.init(B_tile, ldb, rowsB, wave, lane);
+    if constexpr (GATHER_B) lb.template init_gather<PAIR_B>(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
+    else lb.template init<PAIR_B>(B_tile, ldb, rowsB, wave, lane);
     la.issue(smem, 0, K, wave, lane);
     lb.issue(smem + SLAB_A_BYTES, 0, K, wave, lane);
     if (K > BK) {

@@ -20,9 +20,6 @@
 
 namespace llamarl {
 
-constexpr int STAGE_LD = 264;                        // bf16 staging tile row stride (elements): 528 B = 33 chunks
-constexpr int EPI_STAGE_BYTES = BM * STAGE_LD * 2;   // 135168 <= 160 KB
-constexpr int DZ_LDS_BYTES = EPI_STAGE_BYTES > MAINLOOP_LDS_BYTES ? EPI_STAGE_BYTES : MAINLOOP_LDS_BYTES;
 constexpr float LOG2E = 1.4426950408889634f;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -50,13 +47,13 @@ struct FwdArgs {
 };  // partials and zt are indexed by compacted position, not by token
 
 // both operand streams of tile `id` of the logits kernels (rows = W tile, columns = gathered H rows), first two slabs
-template <typename TT, typename Args>
+template <typename TT, bool PAIR = false, typename Args>
 __device__ __forceinline__ void fwd_fetch(TileGemm<TT>& g, const TileSchedule& sch, const Args& a, int id, int n_act,
                                           char* smem) {
   typedef typename TT::store_t st;
   int tv, tt;
   sch.coords(id, tv, tt);
-  g.template prefetch<true>((const st*)a.W + (int64_t)tv * BM * a.d, a.d, (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
+  g.template prefetch<true, PAIR>((const st*)a.W + (int64_t)tv * BM * a.d, a.d, (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
              (int)min((int64_t)BN, (int64_t)n_act - (int64_t)tt * BN), a.d, smem, a.rows + (int64_t)tt * BN, a.N);
 }
 
@@ -270,15 +267,23 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   if (!sch.has_tile()) return;                       // block-uniform: no active token at all
   const int tid = threadIdx.x;
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  // bf16: token columns are fetched pair-interleaved (a lane's two column blocks are neighbouring tokens), so the
+  // vocab-major dz^T leaves straight from registers, 4 bytes per lane and whole 128-byte lines per instruction.
+  constexpr bool PAIR = sizeof(st) == 2;
   TileGemm<TT> g;
-  while (sch.has_tile()) {
-    const int id = sch.take();
-    // the bf16 epilogue stages the whole tile through LDS, so the next tile cannot be fetched under it
-    fwd_fetch<TT>(g, sch, a, id, n_act, smem);
+  int id = sch.take();
+  fwd_fetch<TT, PAIR>(g, sch, a, id, n_act, smem);
+  while (true) {
     f32x16_t acc[TM][TN];
     g.run(smem, acc);
     int tv, tt;
     sch.coords(id, tv, tt);
+    const bool more = sch.has_tile();
+    __syncthreads();                                 // every wave is done reading the slab buffers
+    if (more) {                                      // the epilogue uses no LDS: fetch the next tile under it
+      id = sch.take();
+      fwd_fetch<TT, PAIR>(g, sch, a, id, n_act, smem);
+    }
     const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
     const int rowsV = (int)min((int64_t)BM, a.V - v0);
     const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
@@ -287,7 +292,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
     const int lane_row0 = lp.row(0, 0);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int tok = lp.col(j);
+      const int tok = PAIR ? lp.col_pair() + j : lp.col(j);
       const bool in = tok < rowsT;
       const int64_t t = in ? a.rows[t0 + tok] : 0;
       const float c = in ? a.g * a.coef[t] : 0.f;
@@ -314,37 +319,27 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
 
     // how far the zero padding of each orientation reaches inside this tile
     const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
-    if constexpr (sizeof(st) == 2) {
-      // bf16: only the vocab-major orientation exists (both gradient contractions read it).  Pack pairs of rows
-      // (the fp32 values die here) and stage the tile through LDS so that it leaves as 16-byte chunks of rows.
-      uint32_t pk[TM][TN][8];
+    if constexpr (PAIR) {
+      // bf16: only the vocab-major orientation exists (both gradient contractions read it).  ldzt is a multiple
+      // of 64, so a token pair is never cut by the padding limit.
+      // Uniform 64-bit tile base + 32-bit lane offset, made opaque once per tile so that the 64 row offsets are
+      // not hoisted out of the persistent loop into scratch memory (a 256-row panel of dz^T is < 2 GiB).
+      char* tile_base = reinterpret_cast<char*>(a.dzt) + (v0 * a.ldzt + t0) * 2;
+      const uint32_t ld_b = (uint32_t)a.ldzt * 2u;
+      uint32_t lane_off = (uint32_t)lane_row0 * ld_b + (uint32_t)lp.col_pair() * 2u;
+      asm volatile("" : "+v"(lane_off));
+      const bool in_cols = lp.col_pair() < dzt_cols;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i) {
+        LLAMARL_FENCE();
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int p = 0; p < 8; ++p) pk[i][j][p] = pack_bf16(acc[i][j][2 * p], acc[i][j][2 * p + 1]);
-      __syncthreads();                                         // main-loop LDS reads are over: reuse smem
-      uint16_t* stage = reinterpret_cast<uint16_t*>(smem);     // stage[vocab][token]
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int p = 0; p < 8; ++p) {
-            stage[lp.row(i, 2 * p) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] & 0xffffu);
-            stage[lp.row(i, 2 * p + 1) * STAGE_LD + lp.col(j)] = (uint16_t)(pk[i][j][p] >> 16);
-          }
-      __syncthreads();
-      uint16_t* dzt = reinterpret_cast<uint16_t*>(a.dzt);
-      for (int q = tid; q < BM * (BN / 8); q += NTHREADS) {
-        const int vr = q >> 5, ch = q & 31;
-        if (vr < rowsV && ch * 8 < dzt_cols) {
-          const uint4 v = *reinterpret_cast<const uint4*>(stage + vr * STAGE_LD + ch * 8);
-          *reinterpret_cast<uint4*>(dzt + (v0 + vr) * a.ldzt + t0 + ch * 8) = v;
+        for (int r = 0; r < 16; ++r) {
+          const int rel = i * 32 + (r >> 2) * 8 + (r & 3);
+          if (lane_row0 + rel < rowsV && in_cols)
+            *reinterpret_cast<uint32_t*>(tile_base + (lane_off + (uint32_t)rel * ld_b)) =
+                pack_bf16(acc[i][0][r], acc[i][1][r]);
         }
       }
-      __syncthreads();                                         // staging reads are over before the next prefetch
     } else {
       const int dz_cols = (int)min((int64_t)BM, a.ldz - v0);   // dz[token][vocab]:  token < N, vocab < ldz
       float* dz = reinterpret_cast<float*>(a.dz);
@@ -361,6 +356,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
             if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = v;
           }
     }
+    if (!more) break;
   }
 }
 
@@ -414,7 +410,7 @@ __device__ __forceinline__ void store_fetch(TileGemm<TT>& g, const TileSchedule&
   typedef typename TT::store_t st;
   const StoreTile<TT> t = store_tile_of<TT>(sch, a, id, tiles_m, M, K);
   if (t.k_len > 0)
-    g.template prefetch<false>((const st*)a.A + t.row0 * a.lda + t.k_lo, a.lda, t.rowsA,
+    g.template prefetch<false, true>((const st*)a.A + t.row0 * a.lda + t.k_lo, a.lda, t.rowsA,
                                (const st*)a.B + t.col0 * a.ldb + t.k_lo, a.ldb, t.rowsB, t.k_len, smem);
 }
 // k-major operands: A is At [K][lda] (output rows are its columns), B is Bt [K][ldb]
@@ -464,59 +460,94 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
     }
     const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
     // Store epilogue, one 32-row block at a time (fences keep the unrolled blocks from piling up address registers).
+    // Addresses are a uniform 64-bit tile base plus a 32-bit per-lane byte offset (a 256-row panel is < 2 GiB).
+    // The offset passes through an empty asm once per tile: otherwise the 64 row offsets of a lane, which do not
+    // depend on the tile, are hoisted out of the persistent loop and live in scratch memory.
     constexpr int mode = MODE;
+    constexpr int esz = (mode >= 3) ? 2 : 4;
     char* Cb = reinterpret_cast<char*>(a.C);
     if (mode == 0) Cb += (int64_t)cur.split * a.split_stride * 4;
-    const int esz = (mode >= 3) ? 2 : 4;
     const bool scatter = (mode != 0) && a.c_rows != nullptr;
-    if (mode == 3 && !scatter && cur.rowsB == BN) {
-      // bf16, full-width tile: neighbouring lanes hold neighbouring columns of the same rows.  Lane pairs swap
-      // one value each (DPP quad_perm 1,0,3,2) so that the even lane owns columns (c, c+1) of row r and the odd lane
-      // the same two columns of row r+1: one v_cvt_pk_bf16_f32 and one 4-byte store per two elements.
-      const bool odd = lp.lane & 1;
-      uint16_t* C = reinterpret_cast<uint16_t*>(a.C);
+    const uint32_t ldc_b = (uint32_t)a.ldc * esz;
+    char* tile_base = Cb + (cur.row0 * a.ldc + cur.col0) * esz;
+    const int row_l = lp.row(0, 0);                                // lane's first row; (i, r) adds a constant
+    if constexpr (!KMAJOR) {
+      // K-contiguous operands are fetched pair-interleaved: a lane's two column blocks are neighbouring columns
+      // (c, c+1), so it stores them as one unit and 32 lanes cover 64 consecutive columns of a row -- whole
+      // 128-byte lines per store instruction for bf16 with no cross-lane traffic (stores that split a line over
+      // lanes of different rows measured ~0.5 ms per GB slower).
+      const int c = lp.col_pair();
+      const bool one = c < cur.rowsB, both = c + 1 < cur.rowsB;
+      uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)c * esz;
+      asm volatile("" : "+v"(lane_off));
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         LLAMARL_FENCE();
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          const int rib = lp.row(i, 2 * p) + (odd ? 1 : 0);
-          uint16_t* rowp = C + (cur.row0 + rib) * a.ldc + cur.col0;
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const float own0 = acc[i][j][2 * p], own1 = acc[i][j][2 * p + 1];
-            const float nbr0 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(own0), 0xB1, 0xF, 0xF, true));
-            const float nbr1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(own1), 0xB1, 0xF, 0xF, true));
-            const uint32_t v = pack_bf16(odd ? nbr1 : own0, odd ? own1 : nbr0);
-            if (rib < cur.rowsA) *reinterpret_cast<uint32_t*>(rowp + (lp.col(j) & ~1)) = v;
+        for (int r = 0; r < 16; ++r) {
+          const int rel = i * 32 + (r >> 2) * 8 + (r & 3);
+          const int rib = row_l + rel;
+          if (rib < cur.rowsA && one) {
+            char* q = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + c) * esz
+                              : tile_base + (lane_off + (uint32_t)rel * ldc_b);
+            float v0 = acc[i][0][r], v1 = acc[i][1][r];
+            if (mode <= 2) {
+              float* f = reinterpret_cast<float*>(q);
+              if (both) {
+                if (mode == 2) {
+                  const float2 old = *reinterpret_cast<const float2*>(f);
+                  v0 += old.x;
+                  v1 += old.y;
+                }
+                *reinterpret_cast<float2*>(f) = make_float2(v0, v1);
+              } else {
+                if (mode == 2) v0 += *f;
+                *f = v0;
+              }
+            } else {
+              uint16_t* h = reinterpret_cast<uint16_t*>(q);
+              if (both) {
+                if (mode == 4) {
+                  const uint32_t old = *reinterpret_cast<const uint32_t*>(h);
+                  v0 += bf16_bits_to_float((uint16_t)(old & 0xffffu));
+                  v1 += bf16_bits_to_float((uint16_t)(old >> 16));
+                }
+                *reinterpret_cast<uint32_t*>(h) = pack_bf16(v0, v1);
+              } else {
+                if (mode == 4) v0 += bf16_bits_to_float(*h);
+                *h = float_to_bf16_bits(v0);
+              }
+            }
           }
         }
       }
-      if (!more) break;
-      continue;
-    }
+    } else {
+      // k-major operands keep the plain column order: one element per lane and column block
+      uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)lp.col(0) * esz;
+      asm volatile("" : "+v"(lane_off));
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      LLAMARL_FENCE();
+      for (int i = 0; i < TM; ++i) {
+        LLAMARL_FENCE();
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rib = lp.row(i, r);
-        if (rib < cur.rowsA) {
-          const int64_t crow = scatter ? (int64_t)a.c_rows[cur.row0 + rib] : cur.row0 + rib;
-          char* rowp = Cb + (crow * a.ldc + cur.col0) * esz;
+        for (int r = 0; r < 16; ++r) {
+          const int rel = i * 32 + (r >> 2) * 8 + (r & 3);
+          const int rib = row_l + rel;
+          if (rib < cur.rowsA) {
+            char* rowq = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + lp.col(0)) * esz
+                                 : tile_base + (lane_off + (uint32_t)rel * ldc_b);
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int cib = lp.col(j);
-            if (cib < cur.rowsB) {
-              float v = acc[i][j][r];
-              if (mode <= 2) {
-                float* q = reinterpret_cast<float*>(rowp) + cib;
-                if (mode == 2) v += *q;
-                *q = v;
-              } else {
-                uint16_t* q = reinterpret_cast<uint16_t*>(rowp) + cib;
-                if (mode == 4) v += bf16_bits_to_float(*q);
-                *q = float_to_bf16_bits(v);
+            for (int j = 0; j < TN; ++j) {
+              if (lp.col(j) < cur.rowsB) {
+                float v = acc[i][j][r];
+                if (mode <= 2) {
+                  float* q = reinterpret_cast<float*>(rowq) + j * 32;
+                  if (mode == 2) v += *q;
+                  *q = v;
+                } else {
+                  uint16_t* q = reinterpret_cast<uint16_t*>(rowq) + j * 32;
+                  if (mode == 4) v += bf16_bits_to_float(*q);
+                  *q = float_to_bf16_bits(v);
+                }
               }
             }
           }

@@ -240,7 +240,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   a.tiles_v = (int)((V + BM - 1) / BM);
   a.tiles_t = (int)((N + BN - 1) / BN);
   a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt; a.rows = rows; a.n_act = n_act;
-  const int dz_lds = kBf16 ? DZ_LDS_BYTES : MAINLOOP_LDS_BYTES;
+  const int dz_lds = MAINLOOP_LDS_BYTES;
   HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
   k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
   HIP_TRY(hipGetLastError());
