@@ -193,17 +193,19 @@ struct SlabLoader {
     }
   }
   // k0: first k of the slab (elements); K: contraction length.  lds: start of this operand's slab in LDS.
-  __device__ __forceinline__ void issue(char* lds, int k0, int K, int wave, int lane) const {
+  // TAIL: the slab may reach past K (only the last slab of a contraction whose K is not a multiple of the slab
+  // depth): lanes whose chunk lies past K fetch nothing.  Callers pick TAIL = false wherever they can, it saves a
+  // select per load.
+  __device__ __forceinline__ void issue_one(char* lds, int it, int k0, int K, int wave, int lane, bool tail) const {
     const int soff = k0 * (int)sizeof(typename TT::store_t);
-    // K tail: this lane's chunk lies past K (only in the last slab)
-    const bool cut = k0 + lane_chunk(wave, lane) * TT::EPC >= K;
-    const __amdgpu_buffer_rsrc_t r = rsrc();
+    uint32_t v = voff[it];
+    if (tail) v = (k0 + lane_chunk(wave, lane) * TT::EPC >= K) ? OOB_OFFSET : v;   // `tail` is a constant once inlined
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc(), (lds_void_ptr)(lds + (it * 8 + wave) * 8 * SLAB_ROW_BYTES), 16,
+                                             (int)v, soff, 0, 0);
+  }
+  __device__ __forceinline__ void issue(char* lds, int k0, int K, int wave, int lane) const {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const uint32_t v = cut ? OOB_OFFSET : voff[it];
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(lds + (it * 8 + wave) * 8 * SLAB_ROW_BYTES), 16,
-                                               (int)v, soff, 0, 0);
-    }
+    for (int it = 0; it < 4; ++it) issue_one(lds, it, k0, K, wave, lane, true);
   }
 };
 
@@ -217,14 +219,26 @@ struct Frags {
   typename TT::frag_t b[TN];
 };
 
-// One k-substep: TM x TN MFMA blocks on `cur`; in the shadow of MFMA q the q-th fragment of the next substep is
-// read into `nxt` (A0 B0 A1 B1 ... then the rest of the longer operand).  rd == nullptr: nothing left to read.
+// Loads of one K slab handed to a k-substep, which issues one after each of its MFMAs (8 loads, 8 MFMAs): spread
+// out like this they cost the matrix pipe less than as a burst after the barrier (-4 % time on the bare loop).
 template <typename TT>
+struct SlabFetch {
+  const SlabLoader<TT>* la;
+  const SlabLoader<TT>* lb;
+  char* dst;      // stage that receives the slab
+  int k0, K, wave, lane;
+};
+
+// One k-substep: TM x TN MFMA blocks on `cur`; in the shadow of MFMA q the q-th fragment of the next substep is
+// read into `nxt` (A0 B0 A1 B1 ... then the rest of the longer operand).  FETCH: 0 none, 1 slab loads without a K
+// tail, 2 with.
+template <typename TT, int FETCH = 0>
 __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, const char* rd, int a_addr, int b_addr,
-                                          f32x16_t (&acc)[TM][TN], bool read) {
+                                          f32x16_t (&acc)[TM][TN], bool read, const SlabFetch<TT>* sf = nullptr) {
   typedef typename TT::frag_t frag_t;
   constexpr int NR = TM + TN;
   constexpr int MINAB = TM < TN ? TM : TN;
+  static_assert(TM * TN == 8, "one slab load per MFMA slot");
 #pragma unroll
   for (int q = 0; q < TM * TN; ++q) {
     const int i = q / TN, j = q % TN;
@@ -241,6 +255,11 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
       }
       LLAMARL_FENCE();
     }
+    if constexpr (FETCH != 0) {
+      if (q < 4) sf->la->issue_one(sf->dst, q, sf->k0, sf->K, sf->wave, sf->lane, FETCH == 2);
+      else sf->lb->issue_one(sf->dst + SLAB_A_BYTES, q - 4, sf->k0, sf->K, sf->wave, sf->lane, FETCH == 2);
+      LLAMARL_FENCE();
+    }
   }
 }
 
@@ -254,8 +273,8 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
 // Per slab kt (4 k-substeps s = 0..3, fragment sets f0/f1 alternate):
 //   s=0..2 : MFMAs of substep s, reads of substep s+1 from slab kt
 //   sync   : wait for this thread's share of slab kt+1, barrier (slab kt+1 visible, slab kt no longer read)
-//   issue  : slab kt+2 -> the buffer slab kt just vacated
-//   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1
+//   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1, and one load of slab
+//            kt+2 after each MFMA, into the buffer slab kt just vacated
 //
 // GATHER_B: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
 // tile row r is its row b_rows[r].  PAIR_B: output columns are pair-interleaved over the lane's two column blocks
@@ -309,14 +328,19 @@ struct TileGemm {
     wait_vmcnt0();
     __syncthreads();
     Frags<TT> f0, f1;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-      f0.a[i] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + i * 32 * SLAB_ROW_BYTES);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-      f0.b[j] = *reinterpret_cast<const frag_t*>(smem + b_addr[0] + j * 32 * SLAB_ROW_BYTES);
+    // same order as the reads of a k-substep (A0 B0 A1 B1 A2 A3), so that the wait counts the compiler derives for
+    // the loop head agree on both ways into it
+    static_assert(TM == 4 && TN == 2, "read order written out for a 4 x 2 wave tile");
+    f0.a[0] = *reinterpret_cast<const frag_t*>(smem + a_addr[0]);
+    f0.b[0] = *reinterpret_cast<const frag_t*>(smem + b_addr[0]);
+    f0.a[1] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + 32 * SLAB_ROW_BYTES);
+    f0.b[1] = *reinterpret_cast<const frag_t*>(smem + b_addr[0] + 32 * SLAB_ROW_BYTES);
+    f0.a[2] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + 2 * 32 * SLAB_ROW_BYTES);
+    f0.a[3] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + 3 * 32 * SLAB_ROW_BYTES);
 
-    for (int kt = 0; kt < nk - 1; ++kt) {
+    // slabs 0 .. nk-3: each fetches slab kt+2.  Then slab nk-2 (nothing left to fetch) and the last slab, written
+    // out one after the other: a branch inside one loop body made the compiler copy the accumulators around.
+    for (int kt = 0; kt < nk - 2; ++kt) {
       char* cur = smem + (kt & 1) * STAGE_BYTES;
       char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
@@ -325,10 +349,19 @@ struct TileGemm {
       k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
       wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
       __syncthreads();    // everyone's has, and everyone is done reading slab kt
-      if (kt + 2 < nk) {
-        la.issue(cur, (kt + 2) * BK, K, wave, lane);
-        lb.issue(cur + SLAB_A_BYTES, (kt + 2) * BK, K, wave, lane);
-      }
+      LLAMARL_FENCE();
+      const SlabFetch<TT> sf{&la, &lb, cur, (kt + 2) * BK, K, wave, lane};
+      k_substep<TT, 2>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true, &sf);
+    }
+    if (nk >= 2) {
+      const char* cur = smem + ((nk - 2) & 1) * STAGE_BYTES;
+      const char* nxt = smem + ((nk - 1) & 1) * STAGE_BYTES;
+      LLAMARL_FENCE();
+      k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
+      k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
+      k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
+      wait_vmcnt0();
+      __syncthreads();
       LLAMARL_FENCE();
       k_substep<TT>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true);
     }

@@ -62,19 +62,30 @@ struct KMajorLoader {
     const int c = km_pi((lane & 31) ^ (2 * (r & 3)));
     voff = (uint32_t)r * row_bytes + (uint32_t)c * 16u;
   }
-  // slab kt of a K range of k_len rows -> lds
-  __device__ __forceinline__ void issue(char* lds, int kt, int k_len, int wave) const {
+  // slab kt of a K range of k_len rows -> lds: the descriptor (uniform) once, then four loads
+  struct Slab {
+    i32x4_t rs;
+    uint32_t lds0;
+  };
+  __device__ __forceinline__ Slab slab(char* lds, int kt, int k_len) const {
     const int rows_left = k_len - kt * 64;
     // the range ends with the last k-row that is left: counted from column col0, that is col0 bytes short of
     // rows * row_bytes (a tile that overhangs the right edge wraps into the next row, never past the matrix)
     const uint32_t rows = (uint32_t)(rows_left <= 0 ? 0 : (rows_left < 64 ? rows_left : 64));
     const uint32_t records = rows ? rows * row_bytes - col0_bytes : 0u;
     const uint64_t b = (((uint64_t)base_hi << 32) | base_lo) + (uint64_t)kt * 64u * row_bytes;
-    const i32x4_t rs = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), (int)records, 0x00020000};
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    Slab sl;
+    sl.rs = i32x4_t{(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), (int)records, 0x00020000};
+    sl.lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    return sl;
+  }
+  __device__ __forceinline__ void issue_one(const Slab& sl, int it, int wave) const {
+    lds_dma16(sl.lds0 + (uint32_t)((it * 8 + wave) * 2 * KM_ROW_BYTES), voff, sl.rs, it * 16u * row_bytes);
+  }
+  __device__ __forceinline__ void issue(char* lds, int kt, int k_len, int wave) const {
+    const Slab sl = slab(lds, kt, k_len);
 #pragma unroll
-    for (int it = 0; it < 4; ++it)
-      lds_dma16(lds0 + (uint32_t)((it * 8 + wave) * 2 * KM_ROW_BYTES), voff, rs, it * 16u * row_bytes);
+    for (int it = 0; it < 4; ++it) issue_one(sl, it, wave);
   }
 };
 
@@ -112,9 +123,19 @@ struct TileGemmTN {
     return __builtin_bit_cast(frag_t, v);
   }
 
+  struct Fetch {     // the eight loads of one slab, issued one after each MFMA of a substep
+    const KMajorLoader* la;
+    const KMajorLoader* lb;
+    KMajorLoader::Slab sa, sb;
+    int wave;
+  };
+
   // substep: TM x TN MFMAs on `cur`; the fragments of the next substep are read in their shadow
+  template <bool FETCH = false>
   __device__ __forceinline__ static void substep(const Frags<TT>& cur, Frags<TT>& nxt, const char* rd, const int (&a_off)[TM],
-                                                 const int (&b_off)[TN], int s_bytes, f32x16_t (&acc)[TM][TN], bool read) {
+                                                 const int (&b_off)[TN], int s_bytes, f32x16_t (&acc)[TM][TN], bool read,
+                                                 const Fetch* f = nullptr) {
+    static_assert(TM * TN == 8, "one slab load per MFMA slot");
     constexpr int NR = TM + TN;
     constexpr int MINAB = TM < TN ? TM : TN;
 #pragma unroll
@@ -131,6 +152,11 @@ struct TileGemmTN {
           if (TM > TN) nxt.a[r] = read_frag(rd + a_off[r] + s_bytes);
           else nxt.b[r] = read_frag(rd + b_off[r] + s_bytes);
         }
+        LLAMARL_FENCE();
+      }
+      if constexpr (FETCH) {
+        if (q < 4) f->la->issue_one(f->sa, q, f->wave);
+        else f->lb->issue_one(f->sb, q - 4, f->wave);
         LLAMARL_FENCE();
       }
     }
@@ -167,12 +193,17 @@ struct TileGemmTN {
     wait_vmcnt0();
     __syncthreads();
     Frags<TT> f0, f1;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) f0.a[i] = read_frag(smem + a_off[i]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) f0.b[j] = read_frag(smem + b_off[j]);
+    // same order as the reads of a substep (A0 B0 A1 B1 A2 A3)
+    static_assert(TM == 4 && TN == 2, "read order written out for a 4 x 2 wave tile");
+    f0.a[0] = read_frag(smem + a_off[0]);
+    f0.b[0] = read_frag(smem + b_off[0]);
+    f0.a[1] = read_frag(smem + a_off[1]);
+    f0.b[1] = read_frag(smem + b_off[1]);
+    f0.a[2] = read_frag(smem + a_off[2]);
+    f0.a[3] = read_frag(smem + a_off[3]);
 
-    for (int kt = 0; kt < nk - 1; ++kt) {
+    // slabs 0 .. nk-3 fetch slab kt+2 under their last substep; slab nk-2 and the last slab follow, written out
+    for (int kt = 0; kt < nk - 2; ++kt) {
       char* cur = smem + (kt & 1) * STAGE_BYTES;
       char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
@@ -181,10 +212,19 @@ struct TileGemmTN {
       substep(f0, f1, cur, a_off, b_off, 3 * SUB, acc, true);
       wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
       __syncthreads();    // everyone's has, and everyone is done reading slab kt
-      if (kt + 2 < nk) {
-        la.issue(cur, kt + 2, k_len, wave);
-        lb.issue(cur + SLAB_A_BYTES, kt + 2, k_len, wave);
-      }
+      LLAMARL_FENCE();
+      const Fetch f{&la, &lb, la.slab(cur, kt + 2, k_len), lb.slab(cur + SLAB_A_BYTES, kt + 2, k_len), wave};
+      substep<true>(f1, f0, nxt, a_off, b_off, 0, acc, true, &f);
+    }
+    if (nk >= 2) {
+      const char* cur = smem + ((nk - 2) & 1) * STAGE_BYTES;
+      const char* nxt = smem + ((nk - 1) & 1) * STAGE_BYTES;
+      LLAMARL_FENCE();
+      substep(f0, f1, cur, a_off, b_off, 1 * SUB, acc, true);
+      substep(f1, f0, cur, a_off, b_off, 2 * SUB, acc, true);
+      substep(f0, f1, cur, a_off, b_off, 3 * SUB, acc, true);
+      wait_vmcnt0();
+      __syncthreads();
       LLAMARL_FENCE();
       substep(f1, f0, nxt, a_off, b_off, 0, acc, true);
     }
