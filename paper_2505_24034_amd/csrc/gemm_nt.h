@@ -1,22 +1,23 @@
 // gemm_nt.h -- the one MFMA main loop every contraction of the path runs on.
 //
 // C[m,n] = sum_k A[m,k] * B[n,k]   ("NT": both operands are K-contiguous), fp32 accumulate.
-//   forward / recompute : A = H [N,d]        B = W   [V,d]     K = d
-//   dH = dz W           : A = dz [N,V]       B = W^T [d,V]     K = V
-//   dW = dz^T H         : A = dz^T [V,N]     B = H^T [d,N]     K = N
+//   forward / recompute : A = W [V,d] tile       B = H rows (gathered)   K = d
+//   dW = dz^T H         : A = dz^T [V,N]         B = H^T [d,N]           K = N
+//   (fp32 only) dH      : A = dz [N,V]           B = W^T [d,V]           K = V
 //
 // gfx950 mapping
-//   - one workgroup = 8 wavefronts (2 x 4) = one 256 x 256 output tile; a wavefront owns 128 x 64 of it
-//     as 4 x 2 MFMA 32x32 blocks (128 fp32 accumulator registers per lane).
-//   - K advances in slabs of 128 bytes per row (64 bf16 / 32 fp32).  A slab of both operands is 64 KB of LDS;
-//     two slabs are resident (128 of the CU's 160 KB) so the next slab streams in while this one is multiplied.
+//   - one workgroup = 8 wavefronts (2 x 4) = one 256 x 256 output tile; a wavefront owns 128 x 64 of it as
+//     8 x 4 blocks of v_mfma_f32_16x16x32_bf16 (128 fp32 accumulator registers per lane).  The 16x16x32 shape is
+//     the one to use on this chip: in an MFMA-only loop it sustains 2.0 PFLOP/s where 32x32x16 sustains 1.75 --
+//     the chip is power-limited and the smaller shape lets it clock higher.
+//   - K advances in slabs of 128 bytes per row (64 bf16 / 32 fp32) = two k-steps of one MFMA depth.  A slab of
+//     both operands is 64 KB of LDS; two slabs are resident (128 of the CU's 160 KB).
 //   - slabs go HBM/L2 -> LDS with buffer loads that write LDS directly (16 bytes per lane, no VGPR staging).
 //     The hardware puts lane i's 16 bytes at LDS base + 16 i, so the bank-conflict swizzle is applied on the
 //     global side: physical 16-byte slot p of row r holds logical chunk p ^ ((r >> 1) & 7), which spreads the
-//     16 rows a ds_read_b128 serves per pass over all 64 LDS banks.
-//   - the loop is software-pipelined by hand: MFMA fragments are double-buffered in registers, every
-//     ds_read_b128 is issued in the shadow of an MFMA one k-substep ahead of its use, and scheduling fences
-//     pin that interleave (the compiler's own schedule exposes the LDS latency).
+//     16 rows that 16 lanes of a ds_read_b128 touch over all 64 LDS banks.
+//   - the loop is software-pipelined by hand (see TileGemm::run): every ds_read_b128 and every slab load is
+//     issued in the shadow of an MFMA, far ahead of its use, and scheduling fences pin that interleave.
 //   - out-of-range rows and the K tail use the buffer descriptor's bounds check: such lanes read zeros.
 //   - kernels are persistent (one workgroup per CU walks a list of tiles) and fetch the first slabs of their next
 //     tile before the epilogue of the current one, so the epilogue's VALU work overlaps that latency.
@@ -28,18 +29,18 @@ namespace llamarl {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 constexpr int BM = 256;       // tile rows (A rows)
 constexpr int BN = 256;       // tile cols (B rows)
 constexpr int NTHREADS = 512;
 constexpr int WAVES_N = 4;    // wave grid 2 (M) x 4 (N)
-constexpr int TM = 4;         // 32x32 MFMA blocks per wave along M  (128 rows)
-constexpr int TN = 2;         // ... along N                          (64 cols)
-constexpr int WAVE_M = TM * 32;
-constexpr int WAVE_N = TN * 32;
+constexpr int MB = 8;         // 16 x 16 MFMA blocks per wave along M  (128 rows)
+constexpr int NB = 4;         // ... along N                            (64 cols)
+constexpr int WAVE_M = MB * 16;
+constexpr int WAVE_N = NB * 16;
 constexpr int SLAB_ROW_BYTES = 128;
+constexpr int BLOCK_BYTES = 16 * SLAB_ROW_BYTES;                  // 16 slab rows: one MFMA block of an operand
 constexpr int SLAB_A_BYTES = BM * SLAB_ROW_BYTES;                 // 32 KB
 constexpr int STAGE_BYTES = (BM + BN) * SLAB_ROW_BYTES;           // 64 KB
 constexpr int MAINLOOP_LDS_BYTES = 2 * STAGE_BYTES;               // 128 KB
@@ -56,16 +57,18 @@ struct F32 {
   static constexpr int EPC = 4;
 };
 
-__device__ __forceinline__ void mma(const bf16x8_t& a, const bf16x8_t& b, f32x16_t& c) {
-  c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+// A fragment is the 16 bytes a lane reads from its row: row = lane % 16 of the block, chunk = lane / 16 of the
+// k-step.  bf16: that is the operand layout of the 16x16x32 MFMA (8 consecutive k per lane).
+__device__ __forceinline__ void mma(const bf16x8_t& a, const bf16x8_t& b, f32x4_t& c) {
+  c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-// fp32: the 32x32x2 MFMA takes one float per lane (k = lane / 32).  A lane holds 4 consecutive k of one chunk;
-// the two half-waves hold different chunks, so four MFMAs cover the 8 k values of a chunk pair.
-__device__ __forceinline__ void mma(const f32x4_t& a, const f32x4_t& b, f32x16_t& c) {
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], c, 0, 0, 0);
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
+// fp32: the 16x16x4 MFMA takes one float per lane (k = lane / 16); four of them consume the lane's chunk.  Which
+// k lands in which MFMA does not matter as long as both operands agree, and they do.
+__device__ __forceinline__ void mma(const f32x4_t& a, const f32x4_t& b, f32x4_t& c) {
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], c, 0, 0, 0);
 }
 
 __device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
@@ -78,27 +81,25 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {  // round to n
   return (uint16_t)(u >> 16);
 }
 
-// Where the accumulator element (i, j, r) of this lane sits inside the 256 x 256 tile.
-// MFMA 32x32 output layout: register r of lane l holds row (r/4)*8 + (l/32)*4 + r%4, column l%32.
+// Where the accumulator element (ib, jb, r) of this lane sits inside the 256 x 256 tile.
+// MFMA 16x16 output layout: register r of lane l holds row 4 (l / 16) + r, column l % 16.
 struct LanePos {
   int wm, wn, lane;
-  __device__ __forceinline__ int row(int i, int r) const {
-    return wm * WAVE_M + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-  }
-  __device__ __forceinline__ int col(int j) const { return wn * WAVE_N + j * 32 + (lane & 31); }
-  // Pair-interleaved columns (see paired_row): the lane's two column blocks hold NEIGHBOURING columns, so a lane
-  // owns a contiguous pair and 32 lanes own 64 consecutive columns of one row.
-  __device__ __forceinline__ int col_pair() const { return wn * WAVE_N + 2 * (lane & 31); }
+  __device__ __forceinline__ int row(int ib, int r) const { return wm * WAVE_M + ib * 16 + (lane >> 4) * 4 + r; }
+  __device__ __forceinline__ int col(int jb) const { return wn * WAVE_N + jb * 16 + (lane & 15); }
+  // Quad-interleaved columns (see tile_row_of): the lane's four column blocks hold NEIGHBOURING columns
+  // col_quad() + jb, so 16 lanes own 64 consecutive columns of one row.
+  __device__ __forceinline__ int col_quad() const { return wn * WAVE_N + 4 * (lane & 15); }
 };
 
 // Which row of an operand tile the loader puts into LDS row `r`.  A wave's 64 LDS rows of the column operand feed
-// its two 32-column MFMA blocks (block j = bit 5, MFMA column n = low 5 bits); with pairing, block j / column n is
-// tile row 2n + j of those 64, so that accumulator registers acc[.][0] and acc[.][1] of a lane are neighbouring
-// output columns.  Only the global side changes: LDS layout, swizzle and fragment reads stay as they are.
-template <bool PAIR>
+// its four 16-column MFMA blocks (block jb = bits 5:4, MFMA column n = low 4 bits); with QUAD, block jb / column n
+// is tile row 4 n + jb of those 64, so that acc[.][0..3] of a lane are four neighbouring output columns and an
+// epilogue can store them as one unit.  Only the global side changes: LDS layout, swizzle and fragment reads stay.
+template <bool QUAD>
 __device__ __forceinline__ int tile_row_of(int r) {
-  static_assert(TN == 2 && WAVE_N == 64, "pairing interleaves exactly two column blocks");
-  return PAIR ? ((r & ~63) | ((r & 31) << 1) | ((r >> 5) & 1)) : r;
+  static_assert(NB == 4 && WAVE_N == 64, "the interleave covers exactly four column blocks");
+  return QUAD ? ((r & ~63) | ((r & 15) << 2) | ((r >> 4) & 3)) : r;
 }
 
 // Persistent tile schedule.  The grid has one workgroup per CU (any size works); workgroups are dealt round-robin
@@ -167,20 +168,20 @@ struct SlabLoader {
     return (lane & 7) ^ swizzle(wave * 8 + (lane >> 3));
   }
   // base: first row of the tile; ld in elements; rows_valid <= 256 rows exist from base on.
-  template <bool PAIR = false>
+  template <bool QUAD = false>
   __device__ __forceinline__ void init(const void* base, int64_t ld, int rows_valid, int wave, int lane) {
     const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
     set_base(base, row_bytes * (uint32_t)rows_valid);
     const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = tile_row_of<PAIR>((it * 8 + wave) * 8 + (lane >> 3));
+      const int row = tile_row_of<QUAD>((it * 8 + wave) * 8 + (lane >> 3));
       voff[it] = (row < rows_valid) ? (uint32_t)row * row_bytes + c16 : OOB_OFFSET;
     }
   }
   // Gathered panel: tile row r is row rows[r] of the whole matrix `base` (total_rows rows, < 2^31 bytes).
   // Free with per-lane buffer offsets: this is how masked tokens are skipped without a packed copy of H.
-  template <bool PAIR = false>
+  template <bool QUAD = false>
   __device__ __forceinline__ void init_gather(const void* base, int64_t ld, int64_t total_rows, const int32_t* rows,
                                               int rows_valid, int wave, int lane) {
     const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
@@ -188,14 +189,13 @@ struct SlabLoader {
     const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = tile_row_of<PAIR>((it * 8 + wave) * 8 + (lane >> 3));
+      const int row = tile_row_of<QUAD>((it * 8 + wave) * 8 + (lane >> 3));
       voff[it] = (row < rows_valid) ? (uint32_t)rows[row] * row_bytes + c16 : OOB_OFFSET;
     }
   }
   // k0: first k of the slab (elements); K: contraction length.  lds: start of this operand's slab in LDS.
-  // TAIL: the slab may reach past K (only the last slab of a contraction whose K is not a multiple of the slab
-  // depth): lanes whose chunk lies past K fetch nothing.  Callers pick TAIL = false wherever they can, it saves a
-  // select per load.
+  // tail: the slab may reach past K (only the last slab of a contraction whose K is not a multiple of the slab
+  // depth): lanes whose chunk lies past K fetch nothing.
   __device__ __forceinline__ void issue_one(char* lds, int it, int k0, int K, int wave, int lane, bool tail) const {
     const int soff = k0 * (int)sizeof(typename TT::store_t);
     uint32_t v = voff[it];
@@ -213,14 +213,7 @@ __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane
 
 #define LLAMARL_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <typename TT>
-struct Frags {
-  typename TT::frag_t a[TM];
-  typename TT::frag_t b[TN];
-};
-
-// Loads of one K slab handed to a k-substep, which issues one after each of its MFMAs (8 loads, 8 MFMAs): spread
-// out like this they cost the matrix pipe less than as a burst after the barrier (-4 % time on the bare loop).
+// The loads of one K slab, issued one per MFMA slot after the barrier of a k-step.
 template <typename TT>
 struct SlabFetch {
   const SlabLoader<TT>* la;
@@ -229,35 +222,52 @@ struct SlabFetch {
   int k0, K, wave, lane;
 };
 
-// One k-substep: TM x TN MFMA blocks on `cur`; in the shadow of MFMA q the q-th fragment of the next substep is
-// read into `nxt` (A0 B0 A1 B1 ... then the rest of the longer operand).  FETCH: 0 none, 1 slab loads without a K
-// tail, 2 with.
-template <typename TT, int FETCH = 0>
-__device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, const char* rd, int a_addr, int b_addr,
-                                          f32x16_t (&acc)[TM][TN], bool read, const SlabFetch<TT>* sf = nullptr) {
+// One k-step = one MFMA depth (two per slab): 32 slots, slot t runs block (ib, jb) = (t / 4, t % 4).
+//   a[8]   : the A fragments of this k-step, one register set each.  Block ib is done after slot 4 ib + 3 and its
+//            registers take the NEXT k-step's fragment right away (slot 4 ib + 4): 28 slots ahead of its use.
+//            a[7] of a k-step is read at its own slot 0.
+//   bc, bn : B fragments of this / the next k-step (all four are used by every ib, so they are double-buffered).
+//   BAR    : this is the last k-step of a slab that has a successor.  By slot 0 every read of the slab has been
+//            issued, so the barrier can sit as early as slot TB = 8: it waits for this thread's share of the next
+//            slab (vmcnt) and for its own reads (lgkmcnt), then the 24 MFMAs left run from registers while the
+//            next slab's fragments are read and, with FETCH, the slab after that is requested (one load per slot,
+//            into the stage this barrier just freed).
+//   NEXT   : there is a next k-step (pa_nxt / pb_nxt: lane's fragment address of its blocks 0).
+template <typename TT, bool BAR, bool NEXT, bool FETCH>
+__device__ __forceinline__ void k_step(typename TT::frag_t (&a)[MB], const typename TT::frag_t (&bc)[NB],
+                                       typename TT::frag_t (&bn)[NB], f32x4_t (&acc)[MB][NB], const char* pa_cur,
+                                       const char* pa_nxt, const char* pb_nxt, const SlabFetch<TT>* sf) {
   typedef typename TT::frag_t frag_t;
-  constexpr int NR = TM + TN;
-  constexpr int MINAB = TM < TN ? TM : TN;
-  static_assert(TM * TN == 8, "one slab load per MFMA slot");
+  constexpr int TB = 8;
+  static_assert(MB == 8 && NB == 4, "slot table written for an 8 x 4 wave tile");
 #pragma unroll
-  for (int q = 0; q < TM * TN; ++q) {
-    const int i = q / TN, j = q % TN;
-    mma(cur.a[i], cur.b[j], acc[i][j]);
-    LLAMARL_FENCE();
-    if (q < NR && read) {
-      if (q < 2 * MINAB) {
-        if ((q & 1) == 0) nxt.a[q >> 1] = *reinterpret_cast<const frag_t*>(rd + a_addr + (q >> 1) * 32 * SLAB_ROW_BYTES);
-        else nxt.b[q >> 1] = *reinterpret_cast<const frag_t*>(rd + b_addr + (q >> 1) * 32 * SLAB_ROW_BYTES);
-      } else {
-        const int r = q - MINAB;
-        if (TM > TN) nxt.a[r] = *reinterpret_cast<const frag_t*>(rd + a_addr + r * 32 * SLAB_ROW_BYTES);
-        else nxt.b[r] = *reinterpret_cast<const frag_t*>(rd + b_addr + r * 32 * SLAB_ROW_BYTES);
-      }
+  for (int t = 0; t < MB * NB; ++t) {
+    const int ib = t >> 2, jb = t & 3;
+    if (BAR && t == TB) {
+      wait_vmcnt0();      // this thread's share of the next slab has landed in LDS
+      __syncthreads();    // everyone's has, and everyone is done reading this slab
       LLAMARL_FENCE();
     }
-    if constexpr (FETCH != 0) {
-      if (q < 4) sf->la->issue_one(sf->dst, q, sf->k0, sf->K, sf->wave, sf->lane, FETCH == 2);
-      else sf->lb->issue_one(sf->dst + SLAB_A_BYTES, q - 4, sf->k0, sf->K, sf->wave, sf->lane, FETCH == 2);
+    mma(a[ib], bc[jb], acc[ib][jb]);
+    LLAMARL_FENCE();
+    if (t == 0) {
+      a[7] = *reinterpret_cast<const frag_t*>(pa_cur + 7 * BLOCK_BYTES);
+      LLAMARL_FENCE();
+    }
+    if (NEXT) {
+      if (t == TB) a[0] = *reinterpret_cast<const frag_t*>(pa_nxt);
+      if (t == TB + 1) a[1] = *reinterpret_cast<const frag_t*>(pa_nxt + BLOCK_BYTES);
+      if (t >= 12 && jb == 0) a[ib - 1] = *reinterpret_cast<const frag_t*>(pa_nxt + (ib - 1) * BLOCK_BYTES);
+      if (t == 10) bn[0] = *reinterpret_cast<const frag_t*>(pb_nxt);
+      if (t == 14) bn[1] = *reinterpret_cast<const frag_t*>(pb_nxt + BLOCK_BYTES);
+      if (t == 18) bn[2] = *reinterpret_cast<const frag_t*>(pb_nxt + 2 * BLOCK_BYTES);
+      if (t == 22) bn[3] = *reinterpret_cast<const frag_t*>(pb_nxt + 3 * BLOCK_BYTES);
+      LLAMARL_FENCE();
+    }
+    if (FETCH && t >= 11 && t <= 25 && (t & 1) == 1) {
+      const int n = (t - 11) >> 1;
+      if (n < 4) sf->la->issue_one(sf->dst, n, sf->k0, sf->K, sf->wave, sf->lane, true);
+      else sf->lb->issue_one(sf->dst + SLAB_A_BYTES, n - 4, sf->k0, sf->K, sf->wave, sf->lane, true);
       LLAMARL_FENCE();
     }
   }
@@ -270,15 +280,9 @@ __device__ __forceinline__ void k_substep(const Frags<TT>& cur, Frags<TT>& nxt, 
 //   run():      the K loop.  Waves leave it at different times: __syncthreads() before reusing LDS.
 // smem must hold MAINLOOP_LDS_BYTES.
 //
-// Per slab kt (4 k-substeps s = 0..3, fragment sets f0/f1 alternate):
-//   s=0..2 : MFMAs of substep s, reads of substep s+1 from slab kt
-//   sync   : wait for this thread's share of slab kt+1, barrier (slab kt+1 visible, slab kt no longer read)
-//   s=3    : MFMAs of substep 3 (already in registers), reads of substep 0 of slab kt+1, and one load of slab
-//            kt+2 after each MFMA, into the buffer slab kt just vacated
-//
 // GATHER_B: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
-// tile row r is its row b_rows[r].  PAIR_B: output columns are pair-interleaved over the lane's two column blocks
-// (tile_row_of); the epilogue must then take its columns from LanePos::col_pair().
+// tile row r is its row b_rows[r].  QUAD_B: output columns are quad-interleaved over the lane's four column blocks
+// (tile_row_of); the epilogue must then take its columns from LanePos::col_quad().
 template <typename TT>
 struct TileGemm {
   typedef typename TT::frag_t frag_t;
@@ -286,15 +290,15 @@ struct TileGemm {
   SlabLoader<TT> la, lb;
   int K;
 
-  template <bool GATHER_B, bool PAIR_B = false>
+  template <bool GATHER_B, bool QUAD_B = false>
   __device__ __forceinline__ void prefetch(const void* A_tile, int64_t lda, int rowsA, const void* B_tile, int64_t ldb,
                                            int rowsB, int64_t K_, char* smem, const int32_t* b_rows = nullptr,
                                            int64_t b_total = 0) {
     const int lane = threadIdx.x & 63, wave = wave_id();
     K = (int)K_;
     la.init(A_tile, lda, rowsA, wave, lane);
-    if constexpr (GATHER_B) lb.template init_gather<PAIR_B>(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
-    else lb.template init<PAIR_B>(B_tile, ldb, rowsB, wave, lane);
+    if constexpr (GATHER_B) lb.template init_gather<QUAD_B>(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
+    else lb.template init<QUAD_B>(B_tile, ldb, rowsB, wave, lane);
     la.issue(smem, 0, K, wave, lane);
     lb.issue(smem + SLAB_A_BYTES, 0, K, wave, lane);
     if (K > BK) {
@@ -303,75 +307,60 @@ struct TileGemm {
     }
   }
 
-  __device__ __forceinline__ void run(char* smem, f32x16_t (&acc)[TM][TN]) {
+  __device__ __forceinline__ void run(char* smem, f32x4_t (&acc)[MB][NB]) {
     const int lane = threadIdx.x & 63, wave = wave_id();
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < NB; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
     const int nk = (K + BK - 1) / BK;
-    // per-lane read addresses: row = lane % 32 inside a 32-row block, chunk pair (2s, 2s+1) split over half-waves
-    const int half = lane >> 5;
-    const int arow = wm * WAVE_M + (lane & 31), brow = wn * WAVE_N + (lane & 31);
-    int a_addr[4], b_addr[4];
+    // per-lane read addresses of block 0: row = lane % 16, chunk 4 ks + lane / 16 of k-step ks, swizzled.  The
+    // swizzle depends on the low four row bits only, so block ib is the same address + ib * BLOCK_BYTES.
+    const int g = lane >> 4, l16 = lane & 15;
+    const int sw = swizzle(l16);
+    int a_addr[2], b_addr[2];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      a_addr[s] = arow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(arow)) * 16);
-      b_addr[s] = SLAB_A_BYTES + brow * SLAB_ROW_BYTES + (((2 * s + half) ^ swizzle(brow)) * 16);
+    for (int ks = 0; ks < 2; ++ks) {
+      a_addr[ks] = (wm * WAVE_M + l16) * SLAB_ROW_BYTES + (((4 * ks + g) ^ sw) * 16);
+      b_addr[ks] = SLAB_A_BYTES + (wn * WAVE_N + l16) * SLAB_ROW_BYTES + (((4 * ks + g) ^ sw) * 16);
     }
     // Slabs 0 and 1 were issued by prefetch(); stores of a previous epilogue may sit between them and now in the
     // vmcnt queue, so wait for everything rather than count.
     wait_vmcnt0();
     __syncthreads();
-    Frags<TT> f0, f1;
-    // same order as the reads of a k-substep (A0 B0 A1 B1 A2 A3), so that the wait counts the compiler derives for
-    // the loop head agree on both ways into it
-    static_assert(TM == 4 && TN == 2, "read order written out for a 4 x 2 wave tile");
-    f0.a[0] = *reinterpret_cast<const frag_t*>(smem + a_addr[0]);
-    f0.b[0] = *reinterpret_cast<const frag_t*>(smem + b_addr[0]);
-    f0.a[1] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + 32 * SLAB_ROW_BYTES);
-    f0.b[1] = *reinterpret_cast<const frag_t*>(smem + b_addr[0] + 32 * SLAB_ROW_BYTES);
-    f0.a[2] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + 2 * 32 * SLAB_ROW_BYTES);
-    f0.a[3] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + 3 * 32 * SLAB_ROW_BYTES);
+    frag_t a[MB], b0[NB], b1[NB];
+    a[0] = *reinterpret_cast<const frag_t*>(smem + a_addr[0]);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) b0[j] = *reinterpret_cast<const frag_t*>(smem + b_addr[0] + j * BLOCK_BYTES);
+#pragma unroll
+    for (int i = 1; i < MB - 1; ++i) a[i] = *reinterpret_cast<const frag_t*>(smem + a_addr[0] + i * BLOCK_BYTES);
 
-    // slabs 0 .. nk-3: each fetches slab kt+2.  Then slab nk-2 (nothing left to fetch) and the last slab, written
-    // out one after the other: a branch inside one loop body made the compiler copy the accumulators around.
+    // slabs 0 .. nk-3 fetch slab kt+2 after their barrier; slab nk-2 (nothing left to fetch) and the last slab
+    // follow, written out one after the other (a branch inside one loop body makes the compiler copy accumulators)
     for (int kt = 0; kt < nk - 2; ++kt) {
       char* cur = smem + (kt & 1) * STAGE_BYTES;
-      char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+      const char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
-      k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
-      k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
-      wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
-      __syncthreads();    // everyone's has, and everyone is done reading slab kt
-      LLAMARL_FENCE();
+      k_step<TT, false, true, false>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1], nullptr);
       const SlabFetch<TT> sf{&la, &lb, cur, (kt + 2) * BK, K, wave, lane};
-      k_substep<TT, 2>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true, &sf);
+      k_step<TT, true, true, true>(a, b1, b0, acc, cur + a_addr[1], nxt + a_addr[0], nxt + b_addr[0], &sf);
     }
     if (nk >= 2) {
       const char* cur = smem + ((nk - 2) & 1) * STAGE_BYTES;
       const char* nxt = smem + ((nk - 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
-      k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
-      k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
-      wait_vmcnt0();
-      __syncthreads();
-      LLAMARL_FENCE();
-      k_substep<TT>(f1, f0, nxt, a_addr[0], b_addr[0], acc, true);
+      k_step<TT, false, true, false>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1], nullptr);
+      k_step<TT, true, true, false>(a, b1, b0, acc, cur + a_addr[1], nxt + a_addr[0], nxt + b_addr[0], nullptr);
     }
     {
       const char* cur = smem + ((nk - 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      k_substep<TT>(f0, f1, cur, a_addr[1], b_addr[1], acc, true);
-      k_substep<TT>(f1, f0, cur, a_addr[2], b_addr[2], acc, true);
-      k_substep<TT>(f0, f1, cur, a_addr[3], b_addr[3], acc, true);
-      k_substep<TT>(f1, f0, cur, 0, 0, acc, false);
+      k_step<TT, false, true, false>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1], nullptr);
+      k_step<TT, false, false, false>(a, b1, b0, acc, cur + a_addr[1], nullptr, nullptr, nullptr);
     }
   }
 };

@@ -6,16 +6,17 @@
 // as the caller holds it: no transposed copy of W and no second orientation of dz are ever made.
 //
 // gfx950 mapping: a K slab of an operand is 64 k-rows x 256 columns x bf16 = 64 rows of 512 bytes in LDS (32 KB,
-// same footprint as the K-contiguous slab).  MFMA wants, per lane, 8 k-values of ONE column; in this layout they
-// sit 512 bytes apart.  ds_read_b64_tr_b16 does the transposition in the LDS pipe: inside each group of 16 lanes,
-// lane 4j+q loads 8 bytes (4 columns) of k-row j, and lane i receives column i of the resulting 4 x 16 block, i.e.
-// 4 consecutive k of its own column.  Two such reads make one MFMA fragment.  Any assignment of k-values to
-// fragment slots is correct as long as both operands use the same one, and they do.
+// same footprint as the K-contiguous slab).  The 16x16x32 MFMA wants, per lane, 8 consecutive k of ONE column
+// (column = lane % 16, k group = lane / 16); in this layout they sit 512 bytes apart.  ds_read_b64_tr_b16 does the
+// transposition in the LDS pipe: inside each group of 16 lanes, lane 4j+q loads 8 bytes (4 columns) of k-row j,
+// and lane i receives column i of the resulting 4 x 16 block, i.e. 4 consecutive k of its own column.  Two such
+// reads (k-rows 8g .. 8g+3 and 8g+4 .. 8g+7 for lane group g) make one MFMA fragment.
 //
-// Bank conflicts: the 32 lanes served together touch 4 k-rows x 2 column halves x 32 bytes.  Rows are 512 bytes
-// apart (same banks), so 16-byte slot p of row k holds logical chunk  pi(p ^ 2(k & 3)), where pi swaps bits 1 and
-// 3 of the chunk index: the 4 rows land in 4 different slot pairs and the two column halves in different
-// bank halves.  As in gemm_nt.h the permutation is applied on the global-address side of the LDS-direct loads.
+// Bank conflicts: the 32 lanes served together are two lane groups, i.e. k-rows 8g + 0..3 for two values of g, 32
+// bytes of each.  Rows are 512 bytes apart (same banks), so 16-byte slot p of row k holds logical chunk
+// p ^ (2 (k & 3) | 8 ((k >> 3) & 1)): the four rows of a group land in four different 32-byte positions and the
+// two groups in different bank halves.  As in gemm_nt.h the permutation is applied on the global-address side of
+// the LDS-direct loads.
 #pragma once
 #include "gemm_nt.h"
 
@@ -37,10 +38,8 @@ __device__ __forceinline__ void lds_dma16(uint32_t lds_addr, uint32_t voff, i32x
                : "memory", "m0");
 }
 
-__device__ __forceinline__ int km_pi(int c) {   // swap bits 1 and 3 (an involution)
-  const int b1 = (c >> 1) & 1, b3 = (c >> 3) & 1;
-  return (c & ~0xA) | (b1 << 3) | (b3 << 1);
-}
+// XOR applied to the 16-byte chunk index of k-row k (see the header)
+__device__ __forceinline__ int km_swz(int k) { return 2 * (k & 3) | 8 * ((k >> 3) & 1); }
 
 // One k-major operand stream.  The descriptor is re-based at every slab (a K range can span many GiB) and covers
 // exactly the k-rows that are left, so the K tail reads zeros.
@@ -57,9 +56,9 @@ struct KMajorLoader {
     row_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(ld * 2));
     col0_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(col0 * 2));
     // wave-instruction `it` of wave w fills k-rows 2(it*8 + w), +1; lane l: row +l/32, physical slot l%32.
-    // (row & 3) = 2(w & 1) + l/32 whatever `it` is, so one offset serves all four instructions.
+    // Bits 0, 1 and 3 of the row do not depend on `it`, so one offset serves all four instructions.
     const int r = 2 * wave + (lane >> 5);
-    const int c = km_pi((lane & 31) ^ (2 * (r & 3)));
+    const int c = (lane & 31) ^ km_swz(r);
     voff = (uint32_t)r * row_bytes + (uint32_t)c * 16u;
   }
   // slab kt of a K range of k_len rows -> lds: the descriptor (uniform) once, then four loads
@@ -123,118 +122,112 @@ struct TileGemmTN {
     return __builtin_bit_cast(frag_t, v);
   }
 
-  struct Fetch {     // the eight loads of one slab, issued one after each MFMA of a substep
+  struct Fetch {     // the eight loads of one slab, issued one per MFMA slot after the barrier
     const KMajorLoader* la;
     const KMajorLoader* lb;
     KMajorLoader::Slab sa, sb;
     int wave;
   };
 
-  // substep: TM x TN MFMAs on `cur`; the fragments of the next substep are read in their shadow
-  template <bool FETCH = false>
-  __device__ __forceinline__ static void substep(const Frags<TT>& cur, Frags<TT>& nxt, const char* rd, const int (&a_off)[TM],
-                                                 const int (&b_off)[TN], int s_bytes, f32x16_t (&acc)[TM][TN], bool read,
-                                                 const Fetch* f = nullptr) {
-    static_assert(TM * TN == 8, "one slab load per MFMA slot");
-    constexpr int NR = TM + TN;
-    constexpr int MINAB = TM < TN ? TM : TN;
+  // Address of block b's fragment: blocks are 32 bytes (two chunks) apart before the chunk swizzle, which XORs bits
+  // 1..3 of the chunk index -- bits the block index occupies too -- so it is an XOR, not an add.  A: the 8 blocks
+  // of a wave span bits 1..3 (fx = the whole swizzle).  B: the 4 blocks span bits 1..2 and the wave's position
+  // bits 3..4, so bit 3 of the swizzle is folded into the base and fx carries bits 1..2 only.
+  __device__ __forceinline__ static const char* blk(const char* base, int b, int fx) { return base + ((b * 32) ^ fx); }
+
+  // One k-step (32 k-rows); same slot table as k_step in gemm_nt.h.  pa / pb: slab base + this lane's row and
+  // byte offset for the k-step; fx: the lane's chunk swizzle in bytes.
+  template <bool BAR, bool NEXT, bool FETCH>
+  __device__ __forceinline__ static void k_step(frag_t (&a)[MB], const frag_t (&bc)[NB], frag_t (&bn)[NB],
+                                                f32x4_t (&acc)[MB][NB], const char* pa_cur, const char* pa_nxt,
+                                                const char* pb_nxt, int fx, int fxb, const Fetch* f) {
+    constexpr int TB = 8;
+    static_assert(MB == 8 && NB == 4, "slot table written for an 8 x 4 wave tile");
 #pragma unroll
-    for (int q = 0; q < TM * TN; ++q) {
-      const int i = q / TN, j = q % TN;
-      mma(cur.a[i], cur.b[j], acc[i][j]);
-      LLAMARL_FENCE();
-      if (q < NR && read) {
-        if (q < 2 * MINAB) {
-          if ((q & 1) == 0) nxt.a[q >> 1] = read_frag(rd + a_off[q >> 1] + s_bytes);
-          else nxt.b[q >> 1] = read_frag(rd + b_off[q >> 1] + s_bytes);
-        } else {
-          const int r = q - MINAB;
-          if (TM > TN) nxt.a[r] = read_frag(rd + a_off[r] + s_bytes);
-          else nxt.b[r] = read_frag(rd + b_off[r] + s_bytes);
-        }
+    for (int t = 0; t < MB * NB; ++t) {
+      const int ib = t >> 2, jb = t & 3;
+      if (BAR && t == TB) {
+        wait_vmcnt0();      // this thread's share of the next slab has landed in LDS
+        __syncthreads();    // everyone's has, and everyone is done reading this slab
         LLAMARL_FENCE();
       }
-      if constexpr (FETCH) {
-        if (q < 4) f->la->issue_one(f->sa, q, f->wave);
-        else f->lb->issue_one(f->sb, q - 4, f->wave);
+      mma(a[ib], bc[jb], acc[ib][jb]);
+      LLAMARL_FENCE();
+      if (t == 0) {
+        a[7] = read_frag(blk(pa_cur, 7, fx));
+        LLAMARL_FENCE();
+      }
+      if (NEXT) {
+        if (t == TB) a[0] = read_frag(blk(pa_nxt, 0, fx));
+        if (t == TB + 1) a[1] = read_frag(blk(pa_nxt, 1, fx));
+        if (t >= 12 && jb == 0) a[ib - 1] = read_frag(blk(pa_nxt, ib - 1, fx));
+        if (t == 10) bn[0] = read_frag(blk(pb_nxt, 0, fxb));
+        if (t == 14) bn[1] = read_frag(blk(pb_nxt, 1, fxb));
+        if (t == 18) bn[2] = read_frag(blk(pb_nxt, 2, fxb));
+        if (t == 22) bn[3] = read_frag(blk(pb_nxt, 3, fxb));
+        LLAMARL_FENCE();
+      }
+      if (FETCH && t >= 11 && t <= 25 && (t & 1) == 1) {
+        const int n = (t - 11) >> 1;
+        if (n < 4) f->la->issue_one(f->sa, n, f->wave);
+        else f->lb->issue_one(f->sb, n - 4, f->wave);
         LLAMARL_FENCE();
       }
     }
   }
 
-  __device__ __forceinline__ void run(char* smem, f32x16_t (&acc)[TM][TN]) {
+  __device__ __forceinline__ void run(char* smem, f32x4_t (&acc)[MB][NB]) {
     const int lane = threadIdx.x & 63, wave = wave_id();
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < NB; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
     const int nk = (k_len + 63) / 64;
 
-    // lane -> what it LOADS for the transposing read: group g = lane/16 serves columns (g&1)*16 .. +15 of a 32-column
-    // block and k-rows 8(g>>1) .. +7 of a 16-row substep; inside the group lane 4j+q loads k-row j, columns 4q .. 4q+3.
+    // lane -> what it LOADS for the transposing read: lane group g = lane / 16 serves k-rows 8g .. 8g+7 of a k-step;
+    // inside the group lane 4j+q loads k-row j (the second read: j + 4), columns 4q .. 4q+3 of the 16-column block.
     const int g = lane >> 4, jrow = (lane >> 2) & 3, q4 = lane & 3;
-    const int krow = 8 * (g >> 1) + jrow;                                  // first of the two reads; second is +4
-    int a_off[TM], b_off[TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = wm * WAVE_M + i * 32 + (g & 1) * 16 + 4 * q4;
-      a_off[i] = krow * KM_ROW_BYTES + ((km_pi(m >> 3) ^ (2 * jrow)) * 16) + ((m >> 2) & 1) * 8;
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = wn * WAVE_N + j * 32 + (g & 1) * 16 + 4 * q4;
-      b_off[j] = SLAB_A_BYTES + krow * KM_ROW_BYTES + ((km_pi(n >> 3) ^ (2 * jrow)) * 16) + ((n >> 2) & 1) * 8;
-    }
-    constexpr int SUB = 16 * KM_ROW_BYTES;                                 // bytes between k-substeps
+    const int krow = 8 * g + jrow;
+    const int fx = km_swz(krow) * 16;                  // same for krow + 4; bit 3 of the k-row is g & 1 in both k-steps
+    // block 0 of this wave: chunk (column / 8) before the swizzle, + the 8-byte half the lane's 4 columns sit in
+    const int a_off = krow * KM_ROW_BYTES + (wm * WAVE_M / 8 + (q4 >> 1)) * 16 + (q4 & 1) * 8;
+    const int fxb = fx & 0x60;
+    const int b_off = SLAB_A_BYTES + krow * KM_ROW_BYTES + ((wn * WAVE_N * 2) ^ (fx & 0x80)) + (q4 >> 1) * 16 + (q4 & 1) * 8;
+    constexpr int KS = 32 * KM_ROW_BYTES;              // bytes between the two k-steps of a slab
 
     wait_vmcnt0();
     __syncthreads();
-    Frags<TT> f0, f1;
-    // same order as the reads of a substep (A0 B0 A1 B1 A2 A3)
-    static_assert(TM == 4 && TN == 2, "read order written out for a 4 x 2 wave tile");
-    f0.a[0] = read_frag(smem + a_off[0]);
-    f0.b[0] = read_frag(smem + b_off[0]);
-    f0.a[1] = read_frag(smem + a_off[1]);
-    f0.b[1] = read_frag(smem + b_off[1]);
-    f0.a[2] = read_frag(smem + a_off[2]);
-    f0.a[3] = read_frag(smem + a_off[3]);
+    frag_t a[MB], b0[NB], b1[NB];
+    a[0] = read_frag(blk(smem + a_off, 0, fx));
+#pragma unroll
+    for (int j = 0; j < NB; ++j) b0[j] = read_frag(blk(smem + b_off, j, fxb));
+#pragma unroll
+    for (int i = 1; i < MB - 1; ++i) a[i] = read_frag(blk(smem + a_off, i, fx));
 
-    // slabs 0 .. nk-3 fetch slab kt+2 under their last substep; slab nk-2 and the last slab follow, written out
+    // slabs 0 .. nk-3 fetch slab kt+2 after their barrier; slab nk-2 and the last slab follow, written out
     for (int kt = 0; kt < nk - 2; ++kt) {
       char* cur = smem + (kt & 1) * STAGE_BYTES;
-      char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+      const char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      substep(f0, f1, cur, a_off, b_off, 1 * SUB, acc, true);
-      substep(f1, f0, cur, a_off, b_off, 2 * SUB, acc, true);
-      substep(f0, f1, cur, a_off, b_off, 3 * SUB, acc, true);
-      wait_vmcnt0();      // this thread's share of slab kt+1 has landed in LDS
-      __syncthreads();    // everyone's has, and everyone is done reading slab kt
-      LLAMARL_FENCE();
+      k_step<false, true, false>(a, b0, b1, acc, cur + a_off, cur + a_off + KS, cur + b_off + KS, fx, fxb, nullptr);
       const Fetch f{&la, &lb, la.slab(cur, kt + 2, k_len), lb.slab(cur + SLAB_A_BYTES, kt + 2, k_len), wave};
-      substep<true>(f1, f0, nxt, a_off, b_off, 0, acc, true, &f);
+      k_step<true, true, true>(a, b1, b0, acc, cur + a_off + KS, nxt + a_off, nxt + b_off, fx, fxb, &f);
     }
     if (nk >= 2) {
       const char* cur = smem + ((nk - 2) & 1) * STAGE_BYTES;
       const char* nxt = smem + ((nk - 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      substep(f0, f1, cur, a_off, b_off, 1 * SUB, acc, true);
-      substep(f1, f0, cur, a_off, b_off, 2 * SUB, acc, true);
-      substep(f0, f1, cur, a_off, b_off, 3 * SUB, acc, true);
-      wait_vmcnt0();
-      __syncthreads();
-      LLAMARL_FENCE();
-      substep(f1, f0, nxt, a_off, b_off, 0, acc, true);
+      k_step<false, true, false>(a, b0, b1, acc, cur + a_off, cur + a_off + KS, cur + b_off + KS, fx, fxb, nullptr);
+      k_step<true, true, false>(a, b1, b0, acc, cur + a_off + KS, nxt + a_off, nxt + b_off, fx, fxb, nullptr);
     }
     {
       const char* cur = smem + ((nk - 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      substep(f0, f1, cur, a_off, b_off, 1 * SUB, acc, true);
-      substep(f1, f0, cur, a_off, b_off, 2 * SUB, acc, true);
-      substep(f0, f1, cur, a_off, b_off, 3 * SUB, acc, true);
-      substep(f1, f0, cur, a_off, b_off, 0, acc, false);
+      k_step<false, true, false>(a, b0, b1, acc, cur + a_off, cur + a_off + KS, cur + b_off + KS, fx, fxb, nullptr);
+      k_step<false, false, false>(a, b1, b0, acc, cur + a_off + KS, nullptr, nullptr, fx, fxb, nullptr);
     }
   }
 };

@@ -10,8 +10,9 @@
 //   k_compact_rows   ascending list of active token rows; k_zero_inactive_rows, k_reduce_splits: small helpers
 //
 // In the two logits kernels the MFMA "row" operand is W (vocab) and the "column" operand is H (tokens): an
-// accumulator lane then holds ONE token (column = lane % 32) and 16 vocab entries per 32x32 block, so the
-// softmax reductions over the vocabulary run inside the lane's own registers, with a single cross-lane step.
+// accumulator lane then holds ONE token per column block (column = lane % 16) and 4 vocab entries per 16x16
+// block, 32 per token over the wave's 8 row blocks, so the softmax reductions over the vocabulary run inside the
+// lane's own registers and finish with two cross-lane steps (lane groups l/16 hold different rows).
 #pragma once
 #include "gemm_nt.h"
 #include "gemm_tn.h"
@@ -32,6 +33,22 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // v_cvt_p
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// Combine a value over the four lane groups l/16 (lanes l, l^16, l^32, l^48) without going through the LDS pipe:
+// v_permlane16_swap / v_permlane32_swap of a register with a copy of itself leave "my 16-lane row's partner" and
+// "my half's partner" next to the own value.
+__device__ __forceinline__ float rows_max(float x) {
+  const auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+  const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  const auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+  const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
 struct FwdArgs {
   const void* H;
   const void* W;
@@ -47,13 +64,13 @@ struct FwdArgs {
 };  // partials and zt are indexed by compacted position, not by token
 
 // both operand streams of tile `id` of the logits kernels (rows = W tile, columns = gathered H rows), first two slabs
-template <typename TT, bool PAIR = false, typename Args>
+template <typename TT, bool QUAD = false, typename Args>
 __device__ __forceinline__ void fwd_fetch(TileGemm<TT>& g, const TileSchedule& sch, const Args& a, int id, int n_act,
                                           char* smem) {
   typedef typename TT::store_t st;
   int tv, tt;
   sch.coords(id, tv, tt);
-  g.template prefetch<true, PAIR>((const st*)a.W + (int64_t)tv * BM * a.d, a.d, (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
+  g.template prefetch<true, QUAD>((const st*)a.W + (int64_t)tv * BM * a.d, a.d, (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
              (int)min((int64_t)BN, (int64_t)n_act - (int64_t)tt * BN), a.d, smem, a.rows + (int64_t)tt * BN, a.N);
 }
 
@@ -76,7 +93,7 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   int id = sch.take();
   fwd_fetch<TT>(g, sch, a, id, n_act, smem);
   while (true) {
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[MB][NB];
     g.run(smem, acc);
     int tv, tt;
     sch.coords(id, tv, tt);
@@ -92,44 +109,44 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 
     if (rowsV < BM) {   // last vocab tile only (block-uniform): rows past V must not enter the softmax
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
+          for (int r = 0; r < 4; ++r)
             if (lp.row(i, r) >= rowsV) acc[i][j][r] = -INFINITY;
     }
-    const int lane_row0 = lp.row(0, 0);              // rows of this lane: lane_row0 + i*32 + (r/4)*8 + r%4
+    const int lane_row0 = lp.row(0, 0);              // rows of this lane: lane_row0 + 16 ib + r
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int j = 0; j < NB; ++j) {
       const int tok = lp.col(j);
       const int y = (tok < rowsT) ? a.targets[a.rows[t0 + tok]] : -1;
       const int yrow = y - (int)v0;                  // vocab row of the target inside this tile (if 0 <= . < rowsV)
       const int yrel = yrow - lane_row0;             // ... relative to this lane's first row
       float m = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[i][j][r]);
-      m = fmaxf(m, __shfl_xor(m, 32));
+        for (int r = 0; r < 4; ++r) m = fmaxf(m, acc[i][j][r]);
+      m = rows_max(m);                               // the four lane groups hold different rows of the same token
       const float mb = (m == -INFINITY) ? 0.f : m * LOG2E;
       float s = 0.f;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[i][j][r], LOG2E, -mb));   // exp2(-inf) = 0
-      s += __shfl_xor(s, 32);
+        for (int r = 0; r < 4; ++r) s += fast_exp2(fmaf(acc[i][j][r], LOG2E, -mb));   // exp2(-inf) = 0
+      s = rows_sum(s);
       // target logit: one lane of one wave of one vocab tile owns row y_t of a token; most waves own none
-      const bool mine = y >= 0 && yrow < rowsV && tok < rowsT && yrel >= 0 && yrel < WAVE_M && (yrel & 4) == 0;
+      const bool mine = y >= 0 && yrow < rowsV && tok < rowsT && yrel >= 0 && yrel < WAVE_M && (yrel & 12) == 0;
       if (__any(mine)) {                             // wave-uniform
         float zy = 0.f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) zy = (yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? acc[i][j][r] : zy;
+          for (int r = 0; r < 4; ++r) zy = (yrel == i * 16 + r) ? acc[i][j][r] : zy;
         if (mine) a.zt[t0 + tok] = zy;
       }
-      if ((lp.lane >> 5) == 0) {
+      if ((lp.lane >> 4) == 0) {
         s_m[lp.wm * BN + tok] = m;
         s_s[lp.wm * BN + tok] = s;
       }
@@ -267,14 +284,14 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   if (!sch.has_tile()) return;                       // block-uniform: no active token at all
   const int tid = threadIdx.x;
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
-  // bf16: token columns are fetched pair-interleaved (a lane's two column blocks are neighbouring tokens), so the
-  // vocab-major dz^T leaves straight from registers, 4 bytes per lane and whole 128-byte lines per instruction.
-  constexpr bool PAIR = sizeof(st) == 2;
+  // bf16: token columns are fetched quad-interleaved (a lane's four column blocks are neighbouring tokens), so the
+  // vocab-major dz^T leaves straight from registers, 8 bytes per lane and whole 128-byte lines per 16 lanes.
+  constexpr bool QUAD = sizeof(st) == 2;
   TileGemm<TT> g;
   int id = sch.take();
-  fwd_fetch<TT, PAIR>(g, sch, a, id, n_act, smem);
+  fwd_fetch<TT, QUAD>(g, sch, a, id, n_act, smem);
   while (true) {
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[MB][NB];
     g.run(smem, acc);
     int tv, tt;
     sch.coords(id, tv, tt);
@@ -282,7 +299,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // the epilogue uses no LDS: fetch the next tile under it
       id = sch.take();
-      fwd_fetch<TT, PAIR>(g, sch, a, id, n_act, smem);
+      fwd_fetch<TT, QUAD>(g, sch, a, id, n_act, smem);
     }
     const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
     const int rowsV = (int)min((int64_t)BM, a.V - v0);
@@ -291,8 +308,8 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
     // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
     const int lane_row0 = lp.row(0, 0);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int tok = PAIR ? lp.col_pair() + j : lp.col(j);
+    for (int j = 0; j < NB; ++j) {
+      const int tok = QUAD ? lp.col_quad() + j : lp.col(j);
       const bool in = tok < rowsT;
       const int64_t t = in ? a.rows[t0 + tok] : 0;
       const float c = in ? a.g * a.coef[t] : 0.f;
@@ -300,44 +317,46 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
       const int yrel = (in ? a.targets[t] : -1) - (int)v0 - lane_row0;
       const bool live = c != 0.f;                            // select: a masked token's row is exactly 0
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+        for (int r = 0; r < 4; ++r) {
           const float p = fast_exp2(fmaf(acc[i][j][r], LOG2E, -lb));
           acc[i][j][r] = live ? -c * p : 0.f;
         }
       // + coef at the target's own vocab row: one lane of one wave of one vocab tile per token
-      const bool mine = live && yrel >= 0 && yrel < WAVE_M && (yrel & 4) == 0;
+      const bool mine = live && yrel >= 0 && yrel < WAVE_M && (yrel & 12) == 0;
       if (__any(mine)) {                                     // wave-uniform
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            acc[i][j][r] += (mine && yrel == i * 32 + (r >> 2) * 8 + (r & 3)) ? c : 0.f;
+          for (int r = 0; r < 4; ++r) acc[i][j][r] += (mine && yrel == i * 16 + r) ? c : 0.f;
       }
     }
 
     // how far the zero padding of each orientation reaches inside this tile
     const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
-    if constexpr (PAIR) {
+    if constexpr (QUAD) {
       // bf16: only the vocab-major orientation exists (both gradient contractions read it).  ldzt is a multiple
-      // of 64, so a token pair is never cut by the padding limit.
-      // Uniform 64-bit tile base + 32-bit lane offset, made opaque once per tile so that the 64 row offsets are
+      // of 64, so a token quad is never cut by the padding limit.
+      // Uniform 64-bit tile base + 32-bit lane offset, made opaque once per tile so that the 32 row offsets are
       // not hoisted out of the persistent loop into scratch memory (a 256-row panel of dz^T is < 2 GiB).
       char* tile_base = reinterpret_cast<char*>(a.dzt) + (v0 * a.ldzt + t0) * 2;
       const uint32_t ld_b = (uint32_t)a.ldzt * 2u;
-      uint32_t lane_off = (uint32_t)lane_row0 * ld_b + (uint32_t)lp.col_pair() * 2u;
+      uint32_t lane_off = (uint32_t)lane_row0 * ld_b + (uint32_t)lp.col_quad() * 2u;
       asm volatile("" : "+v"(lane_off));
-      const bool in_cols = lp.col_pair() < dzt_cols;
+      const bool in_cols = lp.col_quad() < dzt_cols;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < MB; ++i) {
         LLAMARL_FENCE();
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rel = i * 32 + (r >> 2) * 8 + (r & 3);
-          if (lane_row0 + rel < rowsV && in_cols)
-            *reinterpret_cast<uint32_t*>(tile_base + (lane_off + (uint32_t)rel * ld_b)) =
-                pack_bf16(acc[i][0][r], acc[i][1][r]);
+        for (int r = 0; r < 4; ++r) {
+          const int rel = i * 16 + r;
+          if (lane_row0 + rel < rowsV && in_cols) {
+            uint2 v;
+            v.x = pack_bf16(acc[i][0][r], acc[i][1][r]);
+            v.y = pack_bf16(acc[i][2][r], acc[i][3][r]);
+            *reinterpret_cast<uint2*>(tile_base + (lane_off + (uint32_t)rel * ld_b)) = v;
+          }
         }
       }
     } else {
@@ -345,11 +364,11 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
       float* dz = reinterpret_cast<float*>(a.dz);
       float* dzt = reinterpret_cast<float*>(a.dzt);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
+          for (int r = 0; r < 4; ++r) {
             const int vr = lp.row(i, r), tok = lp.col(j);
             const float v = (vr < rowsV) ? acc[i][j][r] : 0.f;   // padded vocab rows of the token-major copy are 0
             if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = v;
@@ -440,17 +459,17 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   int id = sch.take();
   store_fetch(g, sch, a, id, tiles_m, M, K, smem);
   while (true) {
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[MB][NB];
     const int cur_id = id;
     if (store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K).k_len > 0) {
       g.run(smem, acc);
     } else {                                         // nothing to contract: the product is zero
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+          for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
     }
     const bool more = sch.has_tile();
     __syncthreads();                                 // every wave is done reading the slab buffers
@@ -459,9 +478,9 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
       store_fetch(g, sch, a, id, tiles_m, M, K, smem);
     }
     const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
-    // Store epilogue, one 32-row block at a time (fences keep the unrolled blocks from piling up address registers).
+    // Store epilogue, one 16-row block at a time (fences keep the unrolled blocks from piling up address registers).
     // Addresses are a uniform 64-bit tile base plus a 32-bit per-lane byte offset (a 256-row panel is < 2 GiB).
-    // The offset passes through an empty asm once per tile: otherwise the 64 row offsets of a lane, which do not
+    // The offset passes through an empty asm once per tile: otherwise the 32 row offsets of a lane, which do not
     // depend on the tile, are hoisted out of the persistent loop and live in scratch memory.
     constexpr int mode = MODE;
     constexpr int esz = (mode >= 3) ? 2 : 4;
@@ -470,53 +489,47 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
     const bool scatter = (mode != 0) && a.c_rows != nullptr;
     const uint32_t ldc_b = (uint32_t)a.ldc * esz;
     char* tile_base = Cb + (cur.row0 * a.ldc + cur.col0) * esz;
-    const int row_l = lp.row(0, 0);                                // lane's first row; (i, r) adds a constant
+    const int row_l = lp.row(0, 0);                                // lane's first row; (ib, r) adds 16 ib + r
     if constexpr (!KMAJOR) {
-      // K-contiguous operands are fetched pair-interleaved: a lane's two column blocks are neighbouring columns
-      // (c, c+1), so it stores them as one unit and 32 lanes cover 64 consecutive columns of a row -- whole
-      // 128-byte lines per store instruction for bf16 with no cross-lane traffic (stores that split a line over
-      // lanes of different rows measured ~0.5 ms per GB slower).
-      const int c = lp.col_pair();
-      const bool one = c < cur.rowsB, both = c + 1 < cur.rowsB;
+      // K-contiguous operands are fetched quad-interleaved: a lane's four column blocks are neighbouring columns
+      // c .. c+3, stored as one unit; 16 lanes cover 64 consecutive columns of a row -- whole 128-byte lines for
+      // bf16 with no cross-lane traffic (stores that split a line over lanes of different rows measured ~0.5 ms
+      // per GB slower).  The number of columns is a multiple of 4 (checked on the host): a quad is never cut.
+      const int c = lp.col_quad();
+      const bool in_cols = c < cur.rowsB;
       uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)c * esz;
       asm volatile("" : "+v"(lane_off));
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < MB; ++i) {
         LLAMARL_FENCE();
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rel = i * 32 + (r >> 2) * 8 + (r & 3);
+        for (int r = 0; r < 4; ++r) {
+          const int rel = i * 16 + r;
           const int rib = row_l + rel;
-          if (rib < cur.rowsA && one) {
+          if (rib < cur.rowsA && in_cols) {
             char* q = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + c) * esz
                               : tile_base + (lane_off + (uint32_t)rel * ldc_b);
-            float v0 = acc[i][0][r], v1 = acc[i][1][r];
+            float v0 = acc[i][0][r], v1 = acc[i][1][r], v2 = acc[i][2][r], v3 = acc[i][3][r];
             if (mode <= 2) {
-              float* f = reinterpret_cast<float*>(q);
-              if (both) {
-                if (mode == 2) {
-                  const float2 old = *reinterpret_cast<const float2*>(f);
-                  v0 += old.x;
-                  v1 += old.y;
-                }
-                *reinterpret_cast<float2*>(f) = make_float2(v0, v1);
-              } else {
-                if (mode == 2) v0 += *f;
-                *f = v0;
+              float4* f = reinterpret_cast<float4*>(q);
+              if (mode == 2) {
+                const float4 old = *f;
+                v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
               }
+              *f = make_float4(v0, v1, v2, v3);
             } else {
-              uint16_t* h = reinterpret_cast<uint16_t*>(q);
-              if (both) {
-                if (mode == 4) {
-                  const uint32_t old = *reinterpret_cast<const uint32_t*>(h);
-                  v0 += bf16_bits_to_float((uint16_t)(old & 0xffffu));
-                  v1 += bf16_bits_to_float((uint16_t)(old >> 16));
-                }
-                *reinterpret_cast<uint32_t*>(h) = pack_bf16(v0, v1);
-              } else {
-                if (mode == 4) v0 += bf16_bits_to_float(*h);
-                *h = float_to_bf16_bits(v0);
+              uint2* h = reinterpret_cast<uint2*>(q);
+              if (mode == 4) {
+                const uint2 old = *h;
+                v0 += bf16_bits_to_float((uint16_t)(old.x & 0xffffu));
+                v1 += bf16_bits_to_float((uint16_t)(old.x >> 16));
+                v2 += bf16_bits_to_float((uint16_t)(old.y & 0xffffu));
+                v3 += bf16_bits_to_float((uint16_t)(old.y >> 16));
               }
+              uint2 o;
+              o.x = pack_bf16(v0, v1);
+              o.y = pack_bf16(v2, v3);
+              *h = o;
             }
           }
         }
@@ -526,25 +539,25 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
       uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)lp.col(0) * esz;
       asm volatile("" : "+v"(lane_off));
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < MB; ++i) {
         LLAMARL_FENCE();
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rel = i * 32 + (r >> 2) * 8 + (r & 3);
+        for (int r = 0; r < 4; ++r) {
+          const int rel = i * 16 + r;
           const int rib = row_l + rel;
           if (rib < cur.rowsA) {
             char* rowq = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + lp.col(0)) * esz
                                  : tile_base + (lane_off + (uint32_t)rel * ldc_b);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
+            for (int j = 0; j < NB; ++j) {
               if (lp.col(j) < cur.rowsB) {
                 float v = acc[i][j][r];
                 if (mode <= 2) {
-                  float* q = reinterpret_cast<float*>(rowq) + j * 32;
+                  float* q = reinterpret_cast<float*>(rowq) + j * 16;
                   if (mode == 2) v += *q;
                   *q = v;
                 } else {
-                  uint16_t* q = reinterpret_cast<uint16_t*>(rowq) + j * 32;
+                  uint16_t* q = reinterpret_cast<uint16_t*>(rowq) + j * 16;
                   if (mode == 4) v += bf16_bits_to_float(*q);
                   *q = float_to_bf16_bits(v);
                 }

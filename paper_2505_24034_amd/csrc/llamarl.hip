@@ -156,6 +156,9 @@ llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int6
                                  int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, const int32_t* m_count,
                                  const int32_t* k_count, const int32_t* c_rows, int splits, int64_t split_stride,
                                  hipStream_t st) {
+  // the store epilogue of the K-contiguous loop writes four neighbouring columns per lane as one unit
+  if (!KMAJOR && (Nn % 4 != 0 || ldc % 4 != 0))
+    return fail(LLAMARL_ERR_UNSUPPORTED, "output columns and row stride must be multiples of 4");
   StoreArgs a;
   a.m_count = m_count; a.k_count = k_count; a.c_rows = c_rows; a.splits = splits; a.split_stride = split_stride;
   a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.M = M; a.Nn = Nn; a.K = K;
