@@ -108,11 +108,15 @@ __device__ __forceinline__ int tile_row_of(int r) {
 // consecutive ones form an 8 x 4 patch that shares A and B panels.  tiles_m x tiles_n is the number of tiles that
 // exist once the device-side active-row count is known.
 struct TileSchedule {
-  int tiles_m, tiles_n;
+  int tiles_m, tiles_n, group_m;
   int next_id, end_id, stride;
-  __device__ __forceinline__ void init(int tiles_m_, int tiles_n_) {
+  // group_m_: rows of a patch.  The 32 workgroups of an XCD work on 32 consecutive ids = group_m x (32 / group_m)
+  // tiles, which load group_m A panels and 32 / group_m B panels: a B panel is shared by group_m tiles, an A panel
+  // by 32 / group_m.  Give the larger share to the operand that has to come from HBM.
+  __device__ __forceinline__ void init(int tiles_m_, int tiles_n_, int group_m_ = 8) {
     tiles_m = tiles_m_;
     tiles_n = tiles_n_;
+    group_m = group_m_;
     const int ntiles = tiles_m * tiles_n;
     const int bid = blockIdx.x, nblk = gridDim.x;
     const int xcd = bid & 7, local = bid >> 3;
@@ -129,11 +133,10 @@ struct TileSchedule {
     return id;
   }
   __device__ __forceinline__ void coords(int id, int& tm, int& tn) const {
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
+    const int per_group = group_m * tiles_n;
     const int g = id / per_group;
-    const int first_m = g * GROUP_M;
-    const int gsize = min(tiles_m - first_m, GROUP_M);
+    const int first_m = g * group_m;
+    const int gsize = min(tiles_m - first_m, group_m);
     const int in_g = id - g * per_group;
     tm = first_m + in_g % gsize;
     tn = in_g / gsize;
