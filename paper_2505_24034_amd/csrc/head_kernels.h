@@ -22,11 +22,10 @@
 namespace llamarl {
 
 constexpr float LOG2E = 1.4426950408889634f;
-// Patch rows (TileSchedule::init) where the row operand is the big one that streams from HBM (W, dz^T) and the
-// column operand (H rows, H^T) stays in cache: a 4 x 8 patch shares every row panel between 8 tiles.  Measured
-// against 8 x 4 at the Llama-3-8B shape: forward -1.4 %, dz -4 %, dW -3 %; 2 x 16 and 16 x 2 are slower.
-constexpr int PATCH_ROWS_BIG_A = 4;
-constexpr int PATCH_ROWS_DH = 8;       // dH: both operands stream from HBM; 8 x 4 measured best (4: +2.5 %, 2: +10 %)
+// Patch rows (TileSchedule::init).  Measured at the Llama-3-8B shape with patches dealt round-robin over the XCDs:
+// logits kernels 4 and 8 tie (2: +1 %); dW 8 (4: +1.6 %, 2: +5 %); dH 8 (4 and 16: +1.7 %).
+constexpr int PATCH_ROWS_LOGITS = 4;
+constexpr int PATCH_ROWS_STORE = 8;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -87,7 +86,7 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   typedef typename TT::store_t st;
   const int n_act = *a.n_act;
   TileSchedule sch;
-  sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_BIG_A);        // token tiles that hold active rows only
+  sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_LOGITS);        // token tiles that hold active rows only
   if (!sch.has_tile()) return;                       // block-uniform
   const int tid = threadIdx.x;
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
@@ -285,7 +284,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   typedef typename TT::store_t st;
   const int n_act = *a.n_act;
   TileSchedule sch;
-  sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_BIG_A);
+  sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_LOGITS);
   if (!sch.has_tile()) return;                       // block-uniform: no active token at all
   const int tid = threadIdx.x;
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
@@ -456,7 +455,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   const int64_t K = a.k_count ? ((int64_t)*a.k_count + 63) / 64 * 64 : a.K;
   const int tiles_m = (int)((M + BM - 1) / BM);
   TileSchedule sch;
-  sch.init(tiles_m * a.splits, a.tiles_n, KMAJOR ? PATCH_ROWS_DH : PATCH_ROWS_BIG_A);
+  sch.init(tiles_m * a.splits, a.tiles_n, PATCH_ROWS_STORE);
   if (!sch.has_tile()) return;                       // block-uniform
   const int tid = threadIdx.x;
   const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
