@@ -207,6 +207,24 @@ struct SlabLoader {
       voff[it] = (row < rows_valid) ? (uint32_t)rows[row] * row_bytes + c16 : OOB_OFFSET;
     }
   }
+  // The four tile rows this lane fetches (one per wave-instruction), for callers that load the gather list
+  // themselves -- in one batch, ahead of time -- and hand the result to init_gathered().
+  template <bool QUAD = false>
+  __device__ __forceinline__ static int lane_tile_row(int it, int wave, int lane) {
+    return tile_row_of<QUAD>((it * 8 + wave) * 8 + (lane >> 3));
+  }
+  // grow[it] = row of the whole matrix that tile row lane_tile_row(it) maps to (any valid row where the tile row
+  // is >= rows_valid: it is not fetched).
+  template <bool QUAD = false>
+  __device__ __forceinline__ void init_gathered(const void* base, int64_t ld, int64_t total_rows, const int (&grow)[4],
+                                                int rows_valid, int wave, int lane) {
+    const uint32_t row_bytes = (uint32_t)(ld * (int64_t)sizeof(typename TT::store_t));
+    set_base(base, (uint32_t)total_rows * row_bytes);
+    const uint32_t c16 = (uint32_t)lane_chunk(wave, lane) * 16u;
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+      voff[it] = (lane_tile_row<QUAD>(it, wave, lane) < rows_valid) ? (uint32_t)grow[it] * row_bytes + c16 : OOB_OFFSET;
+  }
   // k0: first k of the slab (elements); K: contraction length.  lds: start of this operand's slab in LDS.
   // tail: the slab may reach past K (only the last slab of a contraction whose K is not a multiple of the slab
   // depth): lanes whose chunk lies past K fetch nothing.
@@ -313,6 +331,24 @@ struct TileGemm {
     la.init(A_tile, lda, rowsA, wave, lane);
     if constexpr (GATHER_B) lb.template init_gather<QUAD_B>(B_tile, ldb, b_total, b_rows, rowsB, wave, lane);
     else lb.template init<QUAD_B>(B_tile, ldb, rowsB, wave, lane);
+    la.issue(smem, 0, K, wave, lane);
+    lb.issue(smem + SLAB_A_BYTES, 0, K, wave, lane);
+    if (K > BK) {
+      la.issue(smem + STAGE_BYTES, BK, K, wave, lane);
+      lb.issue(smem + STAGE_BYTES + SLAB_A_BYTES, BK, K, wave, lane);
+    }
+  }
+
+  // as prefetch<true, QUAD_B>, with the gather list entries of this lane already in registers (SlabLoader::
+  // init_gathered): no global load stands between the caller's barrier and the first slab request
+  template <bool QUAD_B>
+  __device__ __forceinline__ void prefetch_gathered(const void* A_tile, int64_t lda, int rowsA, const void* B_base,
+                                                    int64_t ldb, int rowsB, int64_t K_, char* smem, const int (&grow)[4],
+                                                    int64_t b_total) {
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    K = (int)K_;
+    la.init(A_tile, lda, rowsA, wave, lane);
+    lb.template init_gathered<QUAD_B>(B_base, ldb, b_total, grow, rowsB, wave, lane);
     la.issue(smem, 0, K, wave, lane);
     lb.issue(smem + SLAB_A_BYTES, 0, K, wave, lane);
     if (K > BK) {

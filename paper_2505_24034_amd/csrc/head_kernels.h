@@ -67,15 +67,31 @@ struct FwdArgs {
   const int32_t* n_act;   // device scalar
 };  // partials and zt are indexed by compacted position, not by token
 
-// both operand streams of tile `id` of the logits kernels (rows = W tile, columns = gathered H rows), first two slabs
-template <typename TT, bool QUAD = false, typename Args>
-__device__ __forceinline__ void fwd_fetch(TileGemm<TT>& g, const TileSchedule& sch, const Args& a, int id, int n_act,
-                                          char* smem) {
+// The logits kernels gather their column operand (H rows) through the active-row list.  The list entries a lane
+// needs for a tile are loaded in ONE batch, branch-free (indices clamped into the list), before the barrier that
+// ends the previous tile; the compiler otherwise serialises them, each behind its own s_waitcnt, and puts them
+// between the barrier and the slab requests.
+template <bool QUAD, typename Args>
+__device__ __forceinline__ void gather_rows(const TileSchedule& sch, const Args& a, int id, int n_act, int (&grow)[4]) {
+  int tv, tt;
+  sch.coords(id, tv, tt);
+  const int lane = threadIdx.x & 63, wave = wave_id();
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int p = tt * BN + SlabLoader<BF16>::lane_tile_row<QUAD>(it, wave, lane);
+    grow[it] = a.rows[min(p, n_act - 1)];
+  }
+}
+// both operand streams of tile `id` (rows = W tile, columns = gathered H rows), first two slabs
+template <typename TT, bool QUAD, typename Args>
+__device__ __forceinline__ void logits_fetch(TileGemm<TT>& g, const TileSchedule& sch, const Args& a, int id, int n_act,
+                                             const int (&grow)[4], char* smem) {
   typedef typename TT::store_t st;
   int tv, tt;
   sch.coords(id, tv, tt);
-  g.template prefetch<true, QUAD>((const st*)a.W + (int64_t)tv * BM * a.d, a.d, (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
-             (int)min((int64_t)BN, (int64_t)n_act - (int64_t)tt * BN), a.d, smem, a.rows + (int64_t)tt * BN, a.N);
+  g.template prefetch_gathered<QUAD>((const st*)a.W + (int64_t)tv * BM * a.d, a.d,
+                                     (int)min((int64_t)BM, a.V - (int64_t)tv * BM), a.H, a.d,
+                                     (int)min((int64_t)BN, (int64_t)n_act - (int64_t)tt * BN), a.d, smem, grow, a.N);
 }
 
 constexpr int FWD_LDS_BYTES = MAINLOOP_LDS_BYTES + 2 * 2 * BN * 4;   // + per-token (max, sum) of the two wave rows
@@ -88,28 +104,46 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
   TileSchedule sch;
   sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_LOGITS);        // token tiles that hold active rows only
   if (!sch.has_tile()) return;                       // block-uniform
-  const int tid = threadIdx.x;
-  const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
   float* s_m = reinterpret_cast<float*>(smem + MAINLOOP_LDS_BYTES);   // [2 waves along the vocabulary][256 tokens]
   float* s_s = s_m + 2 * BN;                                          // outside the slab buffers: see prefetch below
 
   TileGemm<TT> g;
   int id = sch.take();
-  fwd_fetch<TT>(g, sch, a, id, n_act, smem);
+  int grow[4];
+  gather_rows<false>(sch, a, id, n_act, grow);
+  logits_fetch<TT, false>(g, sch, a, id, n_act, grow, smem);
   while (true) {
     f32x4_t acc[MB][NB];
     g.run(smem, acc);
+    // The lane's position is rebuilt from an opaque copy of the thread id after every main loop: otherwise all the
+    // per-lane constants of the epilogue stay live through the loop, are spilled, and every reload waits (vmcnt) for
+    // the slab requests of the next tile as well.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
     int tv, tt;
     sch.coords(id, tv, tt);
     const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
     const int rowsV = (int)min((int64_t)BM, a.V - v0);
     const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
     const bool more = sch.has_tile();
+    // every global load of the tile boundary in two batches: list entries (this tile's tokens, the next tile's
+    // gather rows), then the targets they point to -- all issued before the slab requests below, so that waiting
+    // for them later does not mean waiting for those
+    const int nid = more ? sch.take() : id;
+    gather_rows<false>(sch, a, nid, n_act, grow);
+    int ytok[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) ytok[j] = a.rows[min((int)t0 + lp.col(j), n_act - 1)];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) ytok[j] = a.targets[ytok[j]];
+    LLAMARL_FENCE();
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // start the next tile's first slabs; the epilogue hides them
-      id = sch.take();
-      fwd_fetch<TT>(g, sch, a, id, n_act, smem);
+      id = nid;
+      logits_fetch<TT, false>(g, sch, a, id, n_act, grow, smem);
     }
+    LLAMARL_FENCE();
 
     if (rowsV < BM) {   // last vocab tile only (block-uniform): rows past V must not enter the softmax
 #pragma unroll
@@ -124,7 +158,7 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int tok = lp.col(j);
-      const int y = (tok < rowsT) ? a.targets[a.rows[t0 + tok]] : -1;
+      const int y = (tok < rowsT) ? ytok[j] : -1;
       const int yrow = y - (int)v0;                  // vocab row of the target inside this tile (if 0 <= . < rowsV)
       const int yrel = yrow - lane_row0;             // ... relative to this lane's first row
       float m = -INFINITY;
@@ -286,28 +320,48 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   TileSchedule sch;
   sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_LOGITS);
   if (!sch.has_tile()) return;                       // block-uniform: no active token at all
-  const int tid = threadIdx.x;
-  const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
   // bf16: token columns are fetched quad-interleaved (a lane's four column blocks are neighbouring tokens), so the
   // vocab-major dz^T leaves straight from registers, 8 bytes per lane and whole 128-byte lines per 16 lanes.
   constexpr bool QUAD = sizeof(st) == 2;
   TileGemm<TT> g;
   int id = sch.take();
-  fwd_fetch<TT, QUAD>(g, sch, a, id, n_act, smem);
+  int grow[4];
+  gather_rows<QUAD>(sch, a, id, n_act, grow);
+  logits_fetch<TT, QUAD>(g, sch, a, id, n_act, grow, smem);
   while (true) {
     f32x4_t acc[MB][NB];
     g.run(smem, acc);
+    int tid = threadIdx.x;                           // opaque per tile: see k_fwd_partials
+    asm volatile("" : "+v"(tid));
+    const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
     int tv, tt;
     sch.coords(id, tv, tt);
     const bool more = sch.has_tile();
-    __syncthreads();                                 // every wave is done reading the slab buffers
-    if (more) {                                      // the epilogue uses no LDS: fetch the next tile under it
-      id = sch.take();
-      fwd_fetch<TT, QUAD>(g, sch, a, id, n_act, smem);
-    }
     const int64_t v0 = (int64_t)tv * BM, t0 = (int64_t)tt * BN;
     const int rowsV = (int)min((int64_t)BM, a.V - v0);
     const int rowsT = (int)min((int64_t)BN, (int64_t)n_act - t0);
+    // every global load of the tile boundary in two batches (list entries, then what they point to), all issued
+    // before the slab requests below
+    const int nid = more ? sch.take() : id;
+    gather_rows<QUAD>(sch, a, nid, n_act, grow);
+    int trow[NB];
+    float tcoef[NB], tlse[NB];
+    int ttgt[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) trow[j] = a.rows[min((int)t0 + (QUAD ? lp.col_quad() + j : lp.col(j)), n_act - 1)];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      tcoef[j] = a.coef[trow[j]];
+      tlse[j] = a.lse[trow[j]];
+      ttgt[j] = a.targets[trow[j]];
+    }
+    LLAMARL_FENCE();
+    __syncthreads();                                 // every wave is done reading the slab buffers
+    if (more) {                                      // the epilogue uses no LDS: fetch the next tile under it
+      id = nid;
+      logits_fetch<TT, QUAD>(g, sch, a, id, n_act, grow, smem);
+    }
+    LLAMARL_FENCE();
 
     // dz in place of the logits; per-token scalars live in registers (one token per lane and j)
     const int lane_row0 = lp.row(0, 0);
@@ -315,10 +369,9 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
     for (int j = 0; j < NB; ++j) {
       const int tok = QUAD ? lp.col_quad() + j : lp.col(j);
       const bool in = tok < rowsT;
-      const int64_t t = in ? a.rows[t0 + tok] : 0;
-      const float c = in ? a.g * a.coef[t] : 0.f;
-      const float lb = (c != 0.f) ? a.lse[t] * LOG2E : 0.f;
-      const int yrel = (in ? a.targets[t] : -1) - (int)v0 - lane_row0;
+      const float c = in ? a.g * tcoef[j] : 0.f;
+      const float lb = (c != 0.f) ? tlse[j] * LOG2E : 0.f;
+      const int yrel = (in ? ttgt[j] : -1) - (int)v0 - lane_row0;
       const bool live = c != 0.f;                            // select: a masked token's row is exactly 0
 #pragma unroll
       for (int i = 0; i < MB; ++i)
@@ -481,6 +534,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
       id = sch.take();
       store_fetch(g, sch, a, id, tiles_m, M, K, smem);
     }
+
     const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
     // Store epilogue, one 16-row block at a time (fences keep the unrolled blocks from piling up address registers).
     // Addresses are a uniform 64-bit tile base plus a 32-bit per-lane byte offset (a 256-row panel is < 2 GiB).
