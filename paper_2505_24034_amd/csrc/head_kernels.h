@@ -138,11 +138,15 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) ytok[j] = a.targets[ytok[j]];
     LLAMARL_FENCE();
+    wait_vmcnt0();                                   // see below
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // start the next tile's first slabs; the epilogue hides them
       id = nid;
       logits_fetch<TT, false>(g, sch, a, id, n_act, grow, smem);
     }
+    // From here to the next main loop nothing may wait on vmcnt: the counter is in order, so a wait for any load
+    // (or spill reload) issued before the slab requests turns into a wait for the requests themselves, and the
+    // epilogue would start only when the slabs have arrived.  Hence the explicit wait above.
     LLAMARL_FENCE();
 
     if (rowsV < BM) {   // last vocab tile only (block-uniform): rows past V must not enter the softmax
@@ -356,6 +360,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
       ttgt[j] = a.targets[trow[j]];
     }
     LLAMARL_FENCE();
+    wait_vmcnt0();                                   // nothing may wait on vmcnt after the slab requests: see k_fwd_partials
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // the epilogue uses no LDS: fetch the next tile under it
       id = nid;
@@ -529,11 +534,13 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
           for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
     }
     const bool more = sch.has_tile();
+    wait_vmcnt0();                                   // nothing may wait on vmcnt after the slab requests: see k_fwd_partials
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // the store epilogue uses no LDS: fetch the next tile under it
       id = sch.take();
       store_fetch(g, sch, a, id, tiles_m, M, K, smem);
     }
+    LLAMARL_FENCE();
 
     const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
     // Store epilogue, one 16-row block at a time (fences keep the unrolled blocks from piling up address registers).
