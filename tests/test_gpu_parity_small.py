@@ -25,6 +25,8 @@ def test_config1_tiny_fp32(lib):
     ("bf16_one_tile", synth.scaled(W8, d=64, V=256, B=1, T=256, len_lo=100, len_hi=256)),
     ("bf16_tiny", synth.scaled(W8, d=8, V=3, B=2, T=5, len_lo=1, len_hi=5)),
     ("bf16_many_tiles", synth.scaled(W8, d=1024, V=2304, B=5, T=512, len_lo=64, len_hi=512)),
+    ("bf16_two_slabs", synth.scaled(W8, d=128, V=100, B=2, T=150, len_lo=20, len_hi=150)),      # K loops of exactly 2 slabs
+    ("bf16_three_slabs", synth.scaled(W8, d=136, V=150, B=2, T=90, len_lo=70, len_hi=90)),      # 3 slabs, K tails in all three contractions
     ("bf16_split_k", synth.scaled(W8, d=512, V=16400, B=2, T=310, len_lo=60, len_hi=310)),     # dH split 8-way along V
     ("f32_split_k", synth.scaled(W1, d=260, V=16400, B=1, T=300, len_lo=100, len_hi=300)),
     ("f32_ragged", synth.scaled(W1, d=100, V=777, B=3, T=100, len_lo=10, len_hi=100)),
