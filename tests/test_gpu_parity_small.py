@@ -66,6 +66,39 @@ def test_results_are_bitwise_reproducible(lib):
         assert torch.equal(a[k], b[k]), k
 
 
+def test_whole_path_captured_in_a_hip_graph_replays_the_eager_bits(lib):
+    # the library allocates nothing, never synchronises and launches only on the caller's stream: the three entry
+    # points can be captured once and replayed.  Replays are interleaved with eager work and checked every time.
+    w = synth.scaled(W8, d=512, V=3000, B=2, T=400, len_lo=50, len_hi=400)
+    x = synth.make_inputs(w, "cuda")
+    B, T = x["mask"].shape
+    V = x["W"].shape[0]
+    mask = x["mask"].reshape(-1)
+
+    def path():
+        logp, lse = lib.token_logprobs(x["H"], x["W"], x["targets"], mask)
+        loss, coef, stats = lib.offpolicy_loss_fwd(logp, x["mu_logp"], x["adv"], x["mask"], B, T, rho=1.05,
+                                                   targets=x["targets"], V=V)
+        dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef)
+        return dict(logp=logp, lse=lse, loss=loss, coef=coef, stats=stats, dH=dH, dW=dW)
+
+    eager = {k: v.clone() for k, v in path().items()}          # also warms up every kernel attribute
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = path()
+    for rep in range(3):
+        for v in out.values():
+            v.fill_(float("nan")) if v.is_floating_point() else v.zero_()
+        again = path()                                          # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(out[k], eager[k]), (rep, k)
+            assert torch.equal(again[k], eager[k]), (rep, k)
+
+
 def test_dW_fp32_output_and_accumulation(lib):
     w = synth.scaled(W8, d=256, V=700, B=2, T=300, len_lo=50, len_hi=300)
     x = synth.make_inputs(w, "cuda")
