@@ -24,7 +24,7 @@ def cpu_baseline(x, w, rows):
     """The fp64 oracle as it stands, on `rows` valid token rows of the same batch at full V and d."""
     import numpy as np
     from oracle import aipo_oracle as orc
-    from paper_2505_24034_amd import synth
+    import synth
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -143,7 +143,7 @@ def main():
 
     import torch
     from paper_2505_24034_amd import binding as L
-    from paper_2505_24034_amd import synth
+    import synth
 
     L.load()                                   # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"

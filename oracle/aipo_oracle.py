@@ -1,8 +1,8 @@
 """Plain fp64 CPU oracle for the trainer-side AIPO hot path (numpy only).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, __graft_entry__.smoke() and the
-cpu_baseline leg of bench.py.  It shares no code with the HIP library and never
-sees a value the HIP library produced.
+cpu_baseline leg of bench.py.  It shares no code with the HIP library, and the
+tests hand it inputs of the workload and its own earlier results only.
 
 What it computes (all in float64, no blocking, no fusion, no reordering):
 
@@ -54,7 +54,7 @@ def widen(x):
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     if x.dtype in (np.float32, np.float64):
-        return x.astype(np.float64)
+        return x.astype(np.float64, copy=False)
     raise TypeError("oracle inputs must be float64, float32 or uint16 (bf16 bits), got %s" % x.dtype)
 
 

@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 from oracle import aipo_oracle as orc
-from paper_2505_24034_amd import synth
+import synth
 
 
 def run_hip(lib, x, rho=2.0, norm_mode=0, grad_loss=1.0, clip_mode=0, eps=(0.2, 0.2), dW_dtype=None,

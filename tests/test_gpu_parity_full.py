@@ -1,18 +1,20 @@
 """GPU parity at the full sizes of the five named workloads, in the launch configuration bench.py times.
 
 The oracle cannot form [N,V] logits in fp64 for these shapes, so it is asked for what it can compute one by one:
-  * log-probs / lse / coef / dH for a sample of token rows (each needs only its own logits row),
+  * log-probs / lse of every valid row from one chunked fp64 forward (rows are independent), and from them the
+    loss, coef and statistics at rho = 2 and with the clip engaged (rho = 1, rho = exp(std delta)),
+  * dH for a sample of token rows (each needs only its own logits row),
   * the WHOLE dW of a backward pass whose gradient weight is restricted to a sample of rows (dW is linear in
     coef, so this pins every dW element against the oracle at the full V x d shape),
-and the rest is checked through properties that hold at any size: masked rows exactly zero, loss equal to the
-fp64 sum of coef * logp, vocabulary column sums of dW vanishing, N_valid exact.
+and the rest is checked through properties that hold at any size: masked rows exactly zero, vocabulary column
+sums of dW vanishing, N_valid exact.  No oracle call takes a value the HIP library produced.
 """
 import numpy as np
 import pytest
 import torch
 
 from oracle import aipo_oracle as orc
-from paper_2505_24034_amd import synth
+import synth
 from parity_util import check_grad, f64
 
 pytestmark = pytest.mark.gpu
@@ -33,6 +35,32 @@ def _sample_rows(x, n, rng):
         picks += [r for r in (e, valid[-1] - e) if r in vs]
     extra = rng.choice(valid, size=max(0, n - len(set(picks))), replace=False)
     return np.array(sorted(set(picks) | set(extra.tolist())))[: max(n, len(set(picks)))]
+
+
+def _oracle_forward_over_valid_rows(x, Wd, chunk=1024):
+    """fp64 oracle log-probs / lse of EVERY valid row, in row chunks (rows are independent).  Inputs only: nothing
+    the HIP library produced is read here."""
+    mask_flat = synth.to_oracle(x["mask"]).reshape(-1)
+    N = mask_flat.size
+    valid = np.nonzero(mask_flat)[0]
+    o_logp, o_lse = np.zeros(N), np.zeros(N)
+    for c0 in range(0, valid.size, chunk):
+        r = valid[c0:c0 + chunk]
+        ridx = torch.as_tensor(r, device="cuda")
+        lp, ls = orc.token_logprobs(synth.to_oracle(x["H"][ridx]), Wd, synth.to_oracle(x["targets"][ridx]))
+        o_logp[r], o_lse[r] = lp, ls
+        print("oracle forward rows", c0 + r.size, "/", valid.size, flush=True)
+    return valid, o_logp, o_lse
+
+
+def _check_loss_outputs(got_loss, got_coef, got_stats, o, o_logp):
+    """loss, coef and stats of one llamarl_offpolicy_loss_fwd call against the oracle's (bf16 tolerances)."""
+    assert np.array_equal(f64(got_coef) == 0, o["coef"] == 0)
+    assert np.abs(f64(got_coef) - o["coef"]).max() <= 2.5e-2 * np.abs(o["coef"]).max()
+    assert abs(float(got_loss) - o["loss"]) <= 1e-2 * np.abs(o["coef"] * o_logp).sum()
+    st = f64(got_stats)
+    assert st[0] == o["stats"][0] and st[4] == o["stats"][4]
+    assert np.allclose(st[1:4], o["stats"][1:4], rtol=0, atol=2.5e-2)
 
 
 @pytest.mark.parametrize("name,n_rows,n_dw_rows", [
@@ -61,31 +89,43 @@ def test_full_size_workload(lib, name, n_rows, n_dw_rows):
     assert not bool(logp[dead].any()) and not bool(lse[dead].any()) and not bool(coef[dead].any())
     assert not bool(dH[dead].any())
     assert bool(torch.isfinite(dW).all()) and bool(torch.isfinite(dH).all())
-    terms = coef.double() * logp.double()
-    assert abs(float(loss) - float(terms.sum())) <= 1e-5 * float(terms.abs().sum()) + 1e-7
     colsum = dW.double().sum(dim=0)
     assert float(colsum.abs().max()) <= 1e-2 * float(dW.double().abs().sum(dim=0).max())
 
-    # ---- sampled rows against the oracle
+    # ---- every log-prob, lse, coef, the loss and the statistics against one fp64 forward over all valid rows.
+    # Every argument of every orc.* call below is an input of the workload or an oracle result.
+    Ws = orc.widen(synth.to_oracle(x["W"]))
+    valid, o_logp, o_lse = _oracle_forward_over_valid_rows(x, Ws)
+    assert valid.size == n_valid
+    assert np.abs(f64(logp) - o_logp).max() <= 2e-2
+    assert np.abs(f64(lse) - o_lse).max() <= 2e-2
+    o_mu, o_adv, o_mask = (synth.to_oracle(x[k]) for k in ("mu_logp", "adv", "mask"))
+    o_tg = synth.to_oracle(x["targets"])
+    o = orc.offpolicy_loss_fwd(o_logp, o_mu, o_adv, o_mask, rho, targets=o_tg, V=V)
+    _check_loss_outputs(loss, coef, stats, o, o_logp)
+
+    # ---- the clip engaged at the full shape: rho = 1 (about half the tokens clipped) and rho = exp(std delta)
+    # (about one in six); at the paper's rho in [2,10] it never fires on these inputs
+    delta = (o_logp - orc.widen(o_mu))[valid]
+    for rho_c in (1.0, float(np.exp(delta.std()))):
+        l_c, c_c, s_c = lib.offpolicy_loss_fwd(logp, x["mu_logp"], x["adv"], x["mask"], B, T, rho=rho_c,
+                                               targets=x["targets"], V=V)
+        torch.cuda.synchronize()
+        o_c = orc.offpolicy_loss_fwd(o_logp, o_mu, o_adv, o_mask, rho_c, targets=o_tg, V=V)
+        print("rho %.4f: clipped fraction oracle %.4f, library %.4f" % (rho_c, o_c["stats"][2], float(s_c[2])),
+              flush=True)
+        assert 0.02 < o_c["stats"][2] < 0.98
+        _check_loss_outputs(l_c, c_c, s_c, o_c, o_logp)
+
+    # ---- dH of a sample of rows: oracle backward from the oracle's own lse and coef
     rng = np.random.default_rng(w.seed)
     rows = _sample_rows(x, n_rows, rng)
     ridx = torch.as_tensor(rows, device="cuda")
-    Hs, Ws = synth.to_oracle(x["H"][ridx]), synth.to_oracle(x["W"])
-    tg = synth.to_oracle(x["targets"][ridx])
-    o_logp, o_lse = orc.token_logprobs(Hs, Ws, tg)
-    assert np.abs(f64(logp[ridx]) - o_logp).max() <= 2e-2
-    assert np.abs(f64(lse[ridx]) - o_lse).max() <= 2e-2
-    # oracle coef for the sampled rows: ratio, clip and advantage per token, normaliser from the whole mask
-    full_logp = np.zeros(N)
-    full_logp[rows] = o_logp
-    o = orc.offpolicy_loss_fwd(full_logp, synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]),
-                               synth.to_oracle(x["mask"]), rho)
-    o_coef = o["coef"][rows]
-    assert np.abs(f64(coef[ridx]) - o_coef).max() <= 2.5e-2 * np.abs(o_coef).max()
-    o_dH, _ = orc.offpolicy_loss_bwd(Hs, Ws, tg, o_lse, o_coef)
+    o_dH, _ = orc.offpolicy_loss_bwd(synth.to_oracle(x["H"][ridx]), Ws, o_tg[rows], o_lse[rows], o["coef"][rows])
     check_grad("dH[sampled rows]", f64(dH[ridx]), o_dH, "bf16")
 
-    # ---- the whole dW of a pass whose gradient weight lives on a sample of rows
+    # ---- the whole dW of a pass whose gradient weight lives on a sample of rows (dW is linear in coef): the
+    # library gets its own coef restricted to those rows, the oracle its own
     if n_dw_rows:
         drows = _sample_rows(x, n_dw_rows, rng)
         didx = torch.as_tensor(drows, device="cuda")
@@ -93,9 +133,8 @@ def test_full_size_workload(lib, name, n_rows, n_dw_rows):
         coef_s[didx] = coef[didx]
         dH_s, dW_s = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], lse, coef_s, dW_dtype=torch.float32)
         torch.cuda.synchronize()
-        Hd = synth.to_oracle(x["H"][didx])
-        _, o_dW = orc.offpolicy_loss_bwd(Hd, Ws, synth.to_oracle(x["targets"][didx]), f64(lse[didx]),
-                                         f64(coef[didx]))
+        _, o_dW = orc.offpolicy_loss_bwd(synth.to_oracle(x["H"][didx]), Ws, o_tg[drows], o_lse[drows],
+                                         o["coef"][drows])
         ref = torch.as_tensor(o_dW, device="cuda")
         err = (dW_s.double() - ref)
         fro = float(err.norm() / ref.norm())
@@ -121,15 +160,8 @@ def test_config2_every_output_against_the_oracle(lib):
     torch.cuda.synchronize()
 
     Wd = orc.widen(synth.to_oracle(x["W"]))
-    valid = np.nonzero(synth.to_oracle(mask_flat))[0]
-    o_logp, o_lse = np.zeros(N), np.zeros(N)
+    valid, o_logp, o_lse = _oracle_forward_over_valid_rows(x, Wd)
     chunk = 1024
-    for c0 in range(0, valid.size, chunk):
-        r = valid[c0:c0 + chunk]
-        ridx = torch.as_tensor(r, device="cuda")
-        lp, ls = orc.token_logprobs(synth.to_oracle(x["H"][ridx]), Wd, synth.to_oracle(x["targets"][ridx]))
-        o_logp[r], o_lse[r] = lp, ls
-        print("oracle forward rows", c0 + r.size, "/", valid.size, flush=True)
     assert np.abs(f64(logp) - o_logp).max() <= 2e-2 and np.abs(f64(lse) - o_lse).max() <= 2e-2
     o = orc.offpolicy_loss_fwd(o_logp, synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]),
                                synth.to_oracle(x["mask"]), rho, targets=synth.to_oracle(x["targets"]), V=V)

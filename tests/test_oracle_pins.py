@@ -444,6 +444,89 @@ def test_ppo_mode_matches_torch_autograd_and_has_zero_gradient_outside_bounds(ep
 
 
 # ---------------------------------------------------------------- group-mean baseline (Sec. 6)
+def _brute_ppo(logp, mu, adv, mask, eps_lo, eps_hi, norm_mode):
+    """App. A display equation by case analysis on the sign of the advantage (no min / clip calls):
+    A >= 0: the objective is A * min(r, 1 + eps_hi), so it follows r (gradient -A r / Z) up to the upper bound and
+    is flat above it; A < 0: it is A * max(r, 1 - eps_lo), flat below the lower bound."""
+    B, T = mask.shape
+    lens = [sum(int(mask[b, t] != 0) for t in range(T)) for b in range(B)]
+    n_valid, b_valid = sum(lens), sum(1 for l in lens if l > 0)
+    loss, coef = 0.0, [0.0] * (B * T)
+    sum_r = sum_d = 0.0
+    n_flat = 0
+    for b in range(B):
+        for t in range(T):
+            if mask[b, t] == 0:
+                continue
+            i = b * T + t
+            delta = logp[i] - mu[i]
+            r = math.exp(delta)
+            Z = (max(n_valid, 1), max(b_valid, 1) * lens[b], B)[norm_mode]
+            A = adv[b]
+            if A >= 0:
+                flat = r > 1.0 + eps_hi
+                obj = A * (1.0 + eps_hi) if flat else A * r
+            else:
+                flat = r < 1.0 - eps_lo
+                obj = A * (1.0 - eps_lo) if flat else A * r
+            loss -= obj / Z
+            coef[i] = 0.0 if flat else -A * r / Z
+            n_flat += int(flat)
+            sum_r += r
+            sum_d += delta
+    den = max(n_valid, 1)
+    return loss, coef, [float(n_valid), sum_r / den, n_flat / den, sum_d / den, 0.0]
+
+
+@pytest.mark.parametrize("norm_mode", [orc.NORM_TOKEN_MEAN, orc.NORM_SEQ_MEAN, orc.NORM_SUM_T_MEAN_B])
+@pytest.mark.parametrize("eps", [(0.2, 0.2), (0.1, 0.3)])
+def test_ppo_mode_loss_coef_and_stats_against_python_loop(norm_mode, eps):
+    H, W, tg, mu, adv, mask = _rand_problem(33, B=5, T=7, d=5, V=9)
+    mask[3, :] = 0
+    logp, _ = orc.token_logprobs(H, W, tg, mask.reshape(-1))
+    mu = logp + np.random.default_rng(6).normal(0, 0.3, logp.shape)
+    out = orc.offpolicy_loss_fwd(logp, mu, adv, mask, 2.0, norm_mode, orc.CLIP_PPO, eps[0], eps[1])
+    loss, coef, stats = _brute_ppo(logp, mu, adv, mask, eps[0], eps[1], norm_mode)
+    assert 0.1 < stats[2] < 0.9
+    assert out["loss"] == pytest.approx(loss, rel=1e-12, abs=1e-14)
+    assert np.allclose(out["coef"], coef, rtol=1e-13, atol=0)
+    assert np.allclose(out["stats"], stats, rtol=1e-13, atol=0)       # incl. the clipped-branch fraction, by value
+
+
+@pytest.mark.parametrize("norm_mode", [orc.NORM_TOKEN_MEAN, orc.NORM_SEQ_MEAN, orc.NORM_SUM_T_MEAN_B])
+def test_ppo_mode_gradients_match_torch_autograd_in_every_norm_mode(norm_mode):
+    H, W, tg, mu, adv, mask = _rand_problem(35, B=4, T=6, d=5, V=9)
+    lp, _ = orc.token_logprobs(H, W, tg)
+    mu = lp + np.random.default_rng(8).normal(0, 0.3, lp.shape)
+    out = orc.aipo_step(H, W, tg, mu, adv, mask, 2.0, norm_mode, 1.0, orc.CLIP_PPO, 0.15, 0.25)
+    loss, gH, gW = _torch_loss(H, W, tg, mu, adv, mask, 2.0, norm_mode, orc.CLIP_PPO, (0.15, 0.25))
+    assert out["loss"] == pytest.approx(loss, rel=1e-12)
+    assert np.allclose(out["dH"], gH, rtol=1e-10, atol=1e-14)
+    assert np.allclose(out["dW"], gW, rtol=1e-10, atol=1e-14)
+
+
+def test_aipo_stats_against_python_loop():
+    # mean ratio, clipped fraction (strict r > rho) and mean log-ratio over the valid tokens, by value
+    H, W, tg, mu, adv, mask = _rand_problem(37, B=4, T=9)
+    mask[1, :] = 0
+    logp, _ = orc.token_logprobs(H, W, tg, mask.reshape(-1))
+    mu = logp + np.random.default_rng(10).normal(0, 0.8, logp.shape)
+    B, T = mask.shape
+    for rho in (1.0, 2.0):
+        out = orc.offpolicy_loss_fwd(logp, mu, adv, mask, rho)
+        n = sr = sd = nc = 0
+        for b in range(B):
+            for t in range(T):
+                if mask[b, t]:
+                    dlt = logp[b * T + t] - mu[b * T + t]
+                    n += 1
+                    sr += math.exp(dlt)
+                    sd += dlt
+                    nc += 1 if math.exp(dlt) > rho else 0
+        assert 0 < nc < n
+        assert np.allclose(out["stats"], [n, sr / n, nc / n, sd / n, 0.0], rtol=1e-13, atol=0)
+
+
 def test_group_advantages_closed_forms_and_loop():
     # hand example: rewards (1, 0, 0, 1 | 3, 3, 3, 3 | 2, 0, 0, 0), n = 4
     r = np.array([1, 0, 0, 1, 3, 3, 3, 3, 2, 0, 0, 0], dtype=np.float64)

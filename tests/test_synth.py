@@ -4,7 +4,7 @@ import math
 import numpy as np
 import torch
 
-from paper_2505_24034_amd import synth
+import synth
 
 
 def test_five_named_workloads_have_the_stated_shapes():
