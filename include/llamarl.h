@@ -17,9 +17,11 @@
  *    (a hipStream_t passed as void*; NULL = the default stream).
  *  - Matrices are dense row-major: H [N,d], W [V,d], dH [N,d], dW [V,d].
  *    N = B*T token rows; row t belongs to generation b = t / T.
- *  - Every call validates its arguments on the host first.  On any error it
+ *  - Every call validates its arguments on the host first.  If that fails it
  *    returns a non-zero status, launches nothing and leaves outputs untouched;
  *    llamarl_last_error() then returns a message (thread-local storage).
+ *    LLAMARL_ERR_HIP (a launch the runtime refused) can come after earlier
+ *    kernels of the same call were enqueued: outputs are then undefined.
  *  - Pointers must be 16-byte aligned (anything hipMalloc/torch returns is).
  *  - dtype LLAMARL_BF16 needs d % 8 == 0, LLAMARL_F32 needs d % 4 == 0
  *    (16-byte rows).  N, V are arbitrary (>= 1).  W may exceed 4 GiB; H must be
@@ -160,7 +162,7 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Measurement aid: llamarl_offpolicy_loss_bwd, which in addition records six caller-owned HIP events
+ * MEASUREMENT AID, outside the method: llamarl_offpolicy_loss_bwd, which in addition records six caller-owned HIP events
  * (phase_events[0..5], HOST array of hipEvent_t passed as void*) on `stream`: [0] before the first kernel,
  * [1] after the set-up kernels (active-row list, zeroed dH rows, operand panels), [2] after the recompute + dz
  * kernel, [3] after the dH contraction, [4] after its split reduction, [5] after the dW contraction.  Same results, same
@@ -172,6 +174,17 @@ llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, c
                                                  int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
                                                  llamarl_dtype dW_dt, int accumulate_dW, void* ws, size_t ws_bytes,
                                                  void* stream, void* const* phase_events);
+
+/*
+ * MEASUREMENT AID, outside the method: runs v_mfma_f32_16x16x32_bf16 from registers only (no LDS, no memory
+ * traffic) in the wave shape of the contraction kernels, one workgroup per CU, `iters` times two k-steps of 32
+ * MFMAs per wavefront, and reports the flop it executed.  Timed by the caller, it gives the rate the matrix pipes of
+ * this chip sustain under their own power draw: the ceiling a kernel that also moves operands can approach.
+ *
+ *   sink    device float [1], never written in practice
+ *   flops   HOST pointer, out: floating-point operations of the launch
+ */
+llamarl_status llamarl_mfma_ceiling(int iters, float* sink, double* flops, void* stream);
 
 /*
  * Group-mean baseline (Sec. 6: from one prompt, n generations are sampled and the baseline is the mean of their

@@ -21,7 +21,7 @@ PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
            "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
-           "llamarl_group_advantages", "llamarl_kl_shaped_rewards")
+           "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling")
 
 
 class LlamarlError(RuntimeError):
@@ -67,6 +67,8 @@ def load():
     lib.llamarl_group_advantages.argtypes = [vp, i64, i64, ci, cf, vp, vp]
     lib.llamarl_kl_shaped_rewards.restype = ci
     lib.llamarl_kl_shaped_rewards.argtypes = [vp, vp, vp, vp, i64, i64, cf, vp, vp, vp]
+    lib.llamarl_mfma_ceiling.restype = ci
+    lib.llamarl_mfma_ceiling.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
     return lib
 
@@ -220,3 +222,12 @@ def kl_shaped_rewards(rewards, logp, base_logp, mask, lambda_kl, stream=None):
     _check(lib.llamarl_kl_shaped_rewards(_ptr(rewards), _ptr(logp), _ptr(base_logp), _ptr(mask), B, T,
                                          float(lambda_kl), _ptr(shaped), _ptr(kl), _stream(stream)))
     return shaped, kl
+
+
+def mfma_ceiling(iters, sink, stream=None):
+    """llamarl_mfma_ceiling (measurement aid): enqueues the MFMA-only kernel, returns the flop it executes."""
+    lib = load()
+    _need(sink, torch.float32, "sink")
+    flops = ctypes.c_double()
+    _check(lib.llamarl_mfma_ceiling(int(iters), _ptr(sink), ctypes.byref(flops), _stream(stream)))
+    return float(flops.value)

@@ -22,6 +22,16 @@
 namespace llamarl {
 
 constexpr float LOG2E = 1.4426950408889634f;
+
+// Row pitch (elements) of the two panels that live in list-position space, dz^T [V][.] and H^T [d][.]: the number
+// of active rows rounded up to 64, made an ODD multiple of 64.  It is derived on the device from the active count,
+// so the panels are as narrow as the batch's valid tokens allow (the k-major dH contraction walks one row pitch per
+// k: a pitch sized for all N rows spreads every 64-row slab over 2 MiB of address space), and an odd multiple of
+// 128 bytes never lines rows up on a power-of-two stride.  The workspace is sized for packed_pitch(N).
+__host__ __device__ __forceinline__ int64_t packed_pitch(int64_t n_rows) {
+  const int64_t p = (n_rows + 63) / 64;
+  return ((p & 1) ? p : p + 1) * 64;
+}
 // Patch rows (TileSchedule::init).  Measured at the Llama-3-8B shape with patches dealt round-robin over the XCDs:
 // logits kernels 4 and 8 tie (2: +1 %); dW 8 (4: +1.6 %, 2: +5 %); dH 8 (4 and 16: +1.7 %).
 constexpr int PATCH_ROWS_LOGITS = 4;
@@ -207,18 +217,22 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 }
 
 // lse[t] = log sum over vocab tiles; logp[t] = z[t,y_t] - lse[t], for the active tokens (the compaction pass
-// already wrote 0 for masked / bad-target rows).  256 threads = 64 list positions x 4 slices of the vocab tiles.
-__global__ __launch_bounds__(256) void k_merge_logp(const float* part_m, const float* part_s, const float* zt,
-                                                     const int32_t* rows, const int32_t* n_act, int tiles_v,
-                                                     int64_t n_pad, float* logp, float* lse) {
-  __shared__ float s_M[4][64], s_S[4][64];
-  const int tok = threadIdx.x & 63, sl = threadIdx.x >> 6;
-  const int64_t p = (int64_t)blockIdx.x * 64 + tok;
+// already wrote 0 for masked / bad-target rows).  HBM-bound (8 bytes per token and vocab tile): a block of 1024
+// threads takes 32 list positions x 32 slices of the vocab tiles, so a row of 32 lanes reads one 128-byte line and
+// there are enough loads in flight to stream.
+constexpr int MERGE_TOKENS = 32, MERGE_SLICES = 32;
+__global__ __launch_bounds__(MERGE_TOKENS * MERGE_SLICES) void k_merge_logp(const float* part_m, const float* part_s,
+                                                                            const float* zt, const int32_t* rows,
+                                                                            const int32_t* n_act, int tiles_v,
+                                                                            int64_t n_pad, float* logp, float* lse) {
+  __shared__ float s_M[MERGE_SLICES][MERGE_TOKENS], s_S[MERGE_SLICES][MERGE_TOKENS];
+  const int tok = threadIdx.x % MERGE_TOKENS, sl = threadIdx.x / MERGE_TOKENS;
+  const int64_t p = (int64_t)blockIdx.x * MERGE_TOKENS + tok;
   const int64_t n = *n_act;
-  if ((int64_t)blockIdx.x * 64 >= n) return;        // block-uniform
+  if ((int64_t)blockIdx.x * MERGE_TOKENS >= n) return;        // block-uniform
   float M = -INFINITY, S = 0.f;
   if (p < n) {
-    for (int j = sl; j < tiles_v; j += 4) {
+    for (int j = sl; j < tiles_v; j += MERGE_SLICES) {
       const float m = part_m[(int64_t)j * n_pad + p], s = part_s[(int64_t)j * n_pad + p];
       if (m > M) {
         S = S * __expf(M - m) + s;      // exp(-inf) = 0 on the first tile
@@ -233,11 +247,9 @@ __global__ __launch_bounds__(256) void k_merge_logp(const float* part_m, const f
   __syncthreads();
   if (sl == 0 && p < n) {
     float Mx = s_M[0][tok];
-#pragma unroll
-    for (int q = 1; q < 4; ++q) Mx = fmaxf(Mx, s_M[q][tok]);
+    for (int q = 1; q < MERGE_SLICES; ++q) Mx = fmaxf(Mx, s_M[q][tok]);
     float Sx = 0.f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) Sx += (s_M[q][tok] == -INFINITY) ? 0.f : s_S[q][tok] * expf(s_M[q][tok] - Mx);
+    for (int q = 0; q < MERGE_SLICES; ++q) Sx += (s_M[q][tok] == -INFINITY) ? 0.f : s_S[q][tok] * expf(s_M[q][tok] - Mx);
     const float l = Mx + logf(Sx);
     const int64_t t = rows[p];
     lse[t] = l;
@@ -247,28 +259,48 @@ __global__ __launch_bounds__(256) void k_merge_logp(const float* part_m, const f
 
 // Active-row list.  mode 0 (forward): row t is active if mask[t] != 0 (mask == nullptr: always) and its target
 // is inside [0,V); inactive rows get logp = lse = 0 here.  mode 1 (backward): active if coef[t] != 0.
-// One block: an ordered scan keeps the list ascending, so every later kernel is deterministic.
-__global__ __launch_bounds__(1024) void k_compact_rows(int mode, const uint8_t* mask, const int32_t* targets,
-                                                        int64_t V, const float* coef, int64_t N, int32_t* rows,
-                                                        int32_t* n_act, float* logp, float* lse) {
-  __shared__ int s_wave[16];
+// The list is ascending, so every later kernel is deterministic.  Block b owns rows [b, b+1) * COMPACT_BLOCK_ROWS:
+// it first counts the active rows in front of its range by evaluating the predicate over them (5 bytes a row,
+// served by L2 -- cheaper than a second launch or a cross-block wait for the batch sizes of a trainer step), then
+// scans its own rows in order.  The last block stores the total.
+constexpr int COMPACT_THREADS = 1024;
+constexpr int COMPACT_BLOCK_ROWS = 4 * COMPACT_THREADS;
+
+__device__ __forceinline__ bool row_active(int mode, const uint8_t* mask, const int32_t* targets, int64_t V,
+                                           const float* coef, int64_t t) {
+  if (mode != 0) return coef[t] != 0.f;
+  const int y = targets[t];
+  return (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
+}
+
+__global__ __launch_bounds__(COMPACT_THREADS) void k_compact_rows(int mode, const uint8_t* mask, const int32_t* targets,
+                                                                   int64_t V, const float* coef, int64_t N,
+                                                                   int32_t* rows, int32_t* n_act, float* logp,
+                                                                   float* lse) {
+  __shared__ int s_wave[COMPACT_THREADS / 64];
   __shared__ int s_base;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) s_base = 0;
+  const int64_t first = (int64_t)blockIdx.x * COMPACT_BLOCK_ROWS;
+  int before_block = 0;
+  for (int64_t t = tid; t < first; t += COMPACT_THREADS) before_block += row_active(mode, mask, targets, V, coef, t) ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before_block += __shfl_xor(before_block, o);
+  if (lane == 0) s_wave[wave] = before_block;
   __syncthreads();
-  for (int64_t start = 0; start < N; start += 1024) {
+  if (tid == 0) {
+    int tot = 0;
+    for (int w = 0; w < COMPACT_THREADS / 64; ++w) tot += s_wave[w];
+    s_base = tot;
+  }
+  __syncthreads();
+  for (int64_t start = first; start < min(N, first + COMPACT_BLOCK_ROWS); start += COMPACT_THREADS) {
     const int64_t t = start + tid;
     bool act = false;
     if (t < N) {
-      if (mode == 0) {
-        const int y = targets[t];
-        act = (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
-        if (!act) {
-          logp[t] = 0.f;
-          lse[t] = 0.f;
-        }
-      } else {
-        act = coef[t] != 0.f;
+      act = row_active(mode, mask, targets, V, coef, t);
+      if (mode == 0 && !act) {
+        logp[t] = 0.f;
+        lse[t] = 0.f;
       }
     }
     const unsigned long long b = __ballot(act);
@@ -281,12 +313,12 @@ __global__ __launch_bounds__(1024) void k_compact_rows(int mode, const uint8_t* 
     __syncthreads();
     if (tid == 0) {
       int tot = 0;
-      for (int w = 0; w < 16; ++w) tot += s_wave[w];
+      for (int w = 0; w < COMPACT_THREADS / 64; ++w) tot += s_wave[w];
       s_base += tot;
     }
     __syncthreads();
   }
-  if (tid == 0) *n_act = s_base;
+  if (tid == 0 && blockIdx.x == gridDim.x - 1) *n_act = s_base;
 }
 
 // dH rows of inactive tokens (coef == 0) are exactly zero; the dH contraction only writes the active ones.
@@ -310,8 +342,7 @@ struct DzArgs {
   int tiles_v, tiles_t;
   void* dz;     // [N][ldz]  token-major (type of H/W); columns V..ldz-1 written as zero
   int64_t ldz;
-  void* dzt;    // [V][ldzt] vocab-major; columns N..ldzt-1 written as zero
-  int64_t ldzt;
+  void* dzt;    // [V][packed_pitch(n_act)] vocab-major; columns past the active rows written as zero
   const int32_t* rows;    // active token rows (coef != 0), ascending; dz / dzt are indexed by list position
   const int32_t* n_act;
 };
@@ -321,6 +352,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   typedef typename TT::store_t st;
   const int n_act = *a.n_act;
+  const int64_t ldzt = packed_pitch(n_act);
   TileSchedule sch;
   sch.init(a.tiles_v, (n_act + BN - 1) / BN, PATCH_ROWS_LOGITS);
   if (!sch.has_tile()) return;                       // block-uniform: no active token at all
@@ -396,14 +428,14 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
     }
 
     // how far the zero padding of each orientation reaches inside this tile
-    const int dzt_cols = (int)min((int64_t)BN, a.ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
+    const int dzt_cols = (int)min((int64_t)BN, ldzt - t0);   // dzt[vocab][token]: vocab < V, token < ldzt
     if constexpr (QUAD) {
       // bf16: only the vocab-major orientation exists (both gradient contractions read it).  ldzt is a multiple
       // of 64, so a token quad is never cut by the padding limit.
       // Uniform 64-bit tile base + 32-bit lane offset, made opaque once per tile so that the 32 row offsets are
       // not hoisted out of the persistent loop into scratch memory (a 256-row panel of dz^T is < 2 GiB).
-      char* tile_base = reinterpret_cast<char*>(a.dzt) + (v0 * a.ldzt + t0) * 2;
-      const uint32_t ld_b = (uint32_t)a.ldzt * 2u;
+      char* tile_base = reinterpret_cast<char*>(a.dzt) + (v0 * ldzt + t0) * 2;
+      const uint32_t ld_b = (uint32_t)ldzt * 2u;
       uint32_t lane_off = (uint32_t)lane_row0 * ld_b + (uint32_t)lp.col_quad() * 2u;
       asm volatile("" : "+v"(lane_off));
       const bool in_cols = lp.col_quad() < dzt_cols;
@@ -434,7 +466,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
             const int vr = lp.row(i, r), tok = lp.col(j);
             const float v = (vr < rowsV) ? acc[i][j][r] : 0.f;   // padded vocab rows of the token-major copy are 0
             if (tok < rowsT && vr < dz_cols) dz[(t0 + tok) * a.ldz + v0 + vr] = v;
-            if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * a.ldzt + t0 + tok] = v;
+            if (vr < rowsV && tok < dzt_cols) dzt[(v0 + vr) * ldzt + t0 + tok] = v;
           }
     }
     if (!more) break;
@@ -455,6 +487,8 @@ struct StoreArgs {
   const int32_t* m_count;   // non-null: M = *m_count (device scalar)
   const int32_t* k_count;   // non-null: K = *k_count rounded up to 64 (the operands are zero-padded that far)
   const int32_t* c_rows;    // non-null: output row r goes to row c_rows[r] of C
+  const int32_t* pitch_count;  // non-null: operands flagged below have the row pitch packed_pitch(*pitch_count)
+  int packed_a, packed_b;   // A / B is such a panel (lda / ldb are then ignored)
   int splits;               // > 1: split s contracts its share of the K slabs into the fp32 slice C + s * split_stride
   int64_t split_stride;
 };
@@ -511,6 +545,11 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   typedef typename TT::store_t st;
   const int64_t M = a.m_count ? (int64_t)*a.m_count : a.M;
   const int64_t K = a.k_count ? ((int64_t)*a.k_count + 63) / 64 * 64 : a.K;
+  if (a.pitch_count != nullptr) {                    // kernel arguments are a private copy
+    const int64_t pp = packed_pitch(*a.pitch_count);
+    if (a.packed_a) a.lda = pp;
+    if (a.packed_b) a.ldb = pp;
+  }
   const int tiles_m = (int)((M + BM - 1) / BM);
   TileSchedule sch;
   sch.init(tiles_m * a.splits, a.tiles_n, PATCH_ROWS_STORE);
@@ -662,13 +701,17 @@ __global__ __launch_bounds__(256) void k_reduce_splits(const float* part, int sp
 }
 
 // out[c][p] = in[src(p)][c] for p < R, c < C; out[c][p] = 0 for R <= p < ld_out.
-// rows == nullptr: src(p) = p and R is the host value.  Otherwise src(p) = rows[p], R = *r_count, and only the
-// first R rounded up to 64 columns of `out` are written (the contraction that reads it stops there).
+// rows == nullptr: src(p) = p and R is the host value.  Otherwise src(p) = rows[p], R = *r_count, the row pitch of
+// `out` is packed_pitch(R) (ld_out is the pitch the buffer was sized for) and only the first R rounded up to 64
+// columns of `out` are written (the contraction that reads it stops there).
 template <typename ST>
 __global__ void k_transpose(const ST* in, int64_t R, int64_t C, int64_t ld_in, ST* out, int64_t ld_out,
                             const int32_t* rows, const int32_t* r_count) {
   __shared__ ST tile[64][65];
-  if (rows != nullptr) R = *r_count;
+  if (rows != nullptr) {
+    R = *r_count;
+    ld_out = packed_pitch(R);
+  }
   const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
   if (rows != nullptr && r0 >= R) return;                     // block-uniform
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;     // 256 threads: 64 x 4

@@ -4,11 +4,13 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 
+#include "ceiling_kernel.h"
 #include "head_kernels.h"
 #include "loss_kernels.h"
 
@@ -53,17 +55,19 @@ FwdWs fwd_ws(int64_t N, int64_t V) {
 
 struct LossWs {
   int nblocks;
-  size_t off_len, off_bad, off_part, total;
+  size_t off_len, off_bad, off_part, off_ticket, total;
 };
-LossWs loss_ws(int64_t N) {  // sized for the worst case B = N
+LossWs loss_ws(int64_t N, int64_t B) {  // B generations, N = B * T tokens
   LossWs w;
-  w.nblocks = (int)((N + LOSS_BLOCK_TOKENS - 1) / LOSS_BLOCK_TOKENS);
+  w.nblocks = (int)std::min<int64_t>((N + LOSS_BLOCK_TOKENS - 1) / LOSS_BLOCK_TOKENS, LOSS_MAX_BLOCKS);
   w.off_len = 0;
-  w.off_bad = (size_t)round_up(N * 4, 256);
-  w.off_part = w.off_bad + (size_t)round_up(N * 4, 256);
-  w.total = w.off_part + (size_t)round_up((int64_t)w.nblocks * LOSS_NSUM * 8, 256);
+  w.off_bad = (size_t)round_up(B * 4, 256);
+  w.off_part = w.off_bad + (size_t)round_up(B * 4, 256);
+  w.off_ticket = w.off_part + (size_t)round_up((int64_t)w.nblocks * LOSS_NSUM * 8, 256);
+  w.total = w.off_ticket + 256;
   return w;
 }
+
 
 struct BwdWs {
   int64_t ldz, ldzt;  // padded leading dimensions (elements): V and N rounded up to 64
@@ -74,7 +78,7 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
   BwdWs w;
   const size_t es = esize(dt);
   w.ldz = round_up(V, 64);
-  w.ldzt = round_up(N, 64);
+  w.ldzt = packed_pitch(N);          // the kernels use packed_pitch(active rows) <= this
   // bf16: dz exists in the vocab-major orientation only and W is read as it is (k-major dH contraction);
   // fp32 keeps a token-major dz and a transposed copy of W as well
   const bool both = dt == LLAMARL_F32;
@@ -87,10 +91,11 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
   w.off_part = w.off_nact + 256;
   // dH has few output tiles (N/256 x d/256) with a very long K = V: split K until there are enough work items
   // to fill 256 CUs evenly (at most ~1/16 of the last round idle) whatever the number of active rows turns out to
-  // be.  d % 4 keeps float4 rows.
+  // be, as long as a split keeps at least four K slabs (64 bf16 / 32 fp32 elements each).  d % 4 keeps float4 rows.
   const int64_t tiles = ((N + BM - 1) / BM) * ((d + BN - 1) / BN);
+  const int64_t slabs = dt == LLAMARL_BF16 ? (V + 63) / 64 : w.ldz / 32;
   int s = 1;
-  while (s < 8 && tiles * s < 8192 && (w.ldz / 64) / (s * 2) >= 16) s *= 2;
+  while (s < 8 && tiles * s < 8192 && slabs / (s * 2) >= 4) s *= 2;
   w.dh_splits = s;
   w.total = w.off_part + (s > 1 ? (size_t)round_up((int64_t)s * N * d * 4, 256) : 0);
   return w;
@@ -155,12 +160,13 @@ template <typename TT, bool KMAJOR = false>
 llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t Nn,
                                  int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, const int32_t* m_count,
                                  const int32_t* k_count, const int32_t* c_rows, int splits, int64_t split_stride,
-                                 hipStream_t st) {
+                                 const int32_t* pitch_count, int packed_a, int packed_b, hipStream_t st) {
   // the store epilogue of the K-contiguous loop writes four neighbouring columns per lane as one unit
   if (!KMAJOR && (Nn % 4 != 0 || ldc % 4 != 0))
     return fail(LLAMARL_ERR_UNSUPPORTED, "output columns and row stride must be multiples of 4");
   StoreArgs a;
   a.m_count = m_count; a.k_count = k_count; a.c_rows = c_rows; a.splits = splits; a.split_stride = split_stride;
+  a.pitch_count = pitch_count; a.packed_a = packed_a; a.packed_b = packed_b;
   a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.M = M; a.Nn = Nn; a.K = K;
   const int tiles_m = (int)((M + BM - 1) / BM);      // worst case: every row active
   a.tiles_n = (int)((Nn + BN - 1) / BN);
@@ -190,14 +196,15 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
   int32_t* n_act = reinterpret_cast<int32_t*>(ws + w.off_nact);
   a.rows = rows; a.n_act = n_act;
   // active-token list (mask and target range); inactive rows get logp = lse = 0 here
-  k_compact_rows<<<dim3(1), dim3(1024), 0, st>>>(0, mask, targets, V, nullptr, N, rows, n_act, logp, lse);
+  k_compact_rows<<<dim3((unsigned)((N + COMPACT_BLOCK_ROWS - 1) / COMPACT_BLOCK_ROWS)), dim3(COMPACT_THREADS), 0, st>>>(
+      0, mask, targets, V, nullptr, N, rows, n_act, logp, lse);
   HIP_TRY(hipGetLastError());
   HIP_TRY(set_lds(k_fwd_partials<TT>, FWD_LDS_BYTES));
   k_fwd_partials<TT><<<dim3((unsigned)persistent_grid((int64_t)w.tiles_v * w.tiles_t)), dim3(NTHREADS), FWD_LDS_BYTES,
                        st>>>(a);
   HIP_TRY(hipGetLastError());
-  k_merge_logp<<<dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st>>>(a.part_m, a.part_s, a.zt, rows, n_act,
-                                                                     w.tiles_v, w.n_pad, logp, lse);
+  k_merge_logp<<<dim3((unsigned)((N + MERGE_TOKENS - 1) / MERGE_TOKENS)), dim3(MERGE_TOKENS * MERGE_SLICES), 0, st>>>(
+      a.part_m, a.part_s, a.zt, rows, n_act, w.tiles_v, w.n_pad, logp, lse);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
@@ -220,7 +227,8 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   int32_t* n_act = reinterpret_cast<int32_t*>(ws + w.off_nact);
 
   // tokens that carry gradient (coef != 0), and exact zeros for the dH rows of all the others
-  k_compact_rows<<<dim3(1), dim3(1024), 0, st>>>(1, nullptr, nullptr, V, coef, N, rows, n_act, nullptr, nullptr);
+  k_compact_rows<<<dim3((unsigned)((N + COMPACT_BLOCK_ROWS - 1) / COMPACT_BLOCK_ROWS)), dim3(COMPACT_THREADS), 0, st>>>(
+      1, nullptr, nullptr, V, coef, N, rows, n_act, nullptr, nullptr);
   HIP_TRY(hipGetLastError());
   k_zero_inactive_rows<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(reinterpret_cast<stt*>(dH), coef, N, d);
   HIP_TRY(hipGetLastError());
@@ -242,7 +250,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
   a.tiles_v = (int)((V + BM - 1) / BM);
   a.tiles_t = (int)((N + BN - 1) / BN);
-  a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.ldzt = w.ldzt; a.rows = rows; a.n_act = n_act;
+  a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.rows = rows; a.n_act = n_act;
   const int dz_lds = MAINLOOP_LDS_BYTES;
   HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
   k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
@@ -259,10 +267,10 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   const int32_t* dh_scatter = w.dh_splits > 1 ? nullptr : rows;
   if constexpr (kBf16) {
     s = launch_store_gemm<TT, true>(dzt, w.ldzt, W, d, N, d, V, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
-                                    w.dh_splits, N * d, st);
+                                    w.dh_splits, N * d, n_act, 1, 0, st);
   } else {
     s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
-                              w.dh_splits, N * d, st);
+                              w.dh_splits, N * d, nullptr, 0, 0, st);
   }
   if (s != LLAMARL_OK) return s;
   PHASE_EVENT(3);
@@ -274,7 +282,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   PHASE_EVENT(4);
   // dW [V,d] = dz^T [V,n_act] . H^T[d,n_act]^T          (K = n_act, zero-padded to a multiple of 64)
   s = launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW, nullptr,
-                            n_act, nullptr, 1, 0, st);
+                            n_act, nullptr, 1, 0, n_act, 1, 1, st);
   if (s != LLAMARL_OK) return s;
   PHASE_EVENT(5);
 #undef PHASE_EVENT
@@ -295,7 +303,7 @@ size_t llamarl_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt
       if (V <= 0) return 0;
       return fwd_ws(N, V).total;
     case LLAMARL_PASS_LOSS_FWD:
-      return loss_ws(N).total;
+      return loss_ws(N, N).total;     // sized for the worst case B = N
     case LLAMARL_PASS_LOSS_BWD:
       if (V <= 0 || d <= 0 || (dt != LLAMARL_F32 && dt != LLAMARL_BF16)) return 0;
       return bwd_ws(N, d, V, dt).total;
@@ -321,10 +329,10 @@ llamarl_status llamarl_token_logprobs(const void* H, const void* W, const int32_
   return run_logprobs<F32>(H, W, targets, mask, N, d, V, logp, lse, reinterpret_cast<char*>(ws), st);
 }
 
-llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_logp, const float* adv,
-                                          int adv_per_token, const uint8_t* mask, const int32_t* targets, int64_t V,
-                                          int64_t B, int64_t T, const llamarl_loss_params* p, float* loss,
-                                          float* coef, float* stats, void* ws, size_t ws_bytes, void* stream) {
+static llamarl_status check_loss_args(const float* logp, const float* mu_logp, const float* adv, const uint8_t* mask,
+                                      const int32_t* targets, int64_t V, int64_t B, int64_t T,
+                                      const llamarl_loss_params* p, const float* loss, const float* coef,
+                                      const float* stats) {
   if (!logp || !mu_logp || !adv || !p || !loss || !coef || !stats)
     return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
   if (B <= 0 || T <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "B and T must be positive");
@@ -338,13 +346,17 @@ llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_log
   if (p->clip_mode == LLAMARL_CLIP_PPO && (!(p->eps_lo >= 0.f) || !(p->eps_hi >= 0.f) || p->eps_lo > 1.f))
     return fail(LLAMARL_ERR_INVALID_ARG, "PPO mode needs 0 <= eps_lo <= 1 and eps_hi >= 0");
   if (targets && V <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "targets given but V <= 0");
-  const int64_t N = B * T;
-  const LossWs w = loss_ws(N);
-  if (!ws || ws_bytes < w.total)
-    return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, w.total);
-  if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  char* wsb = reinterpret_cast<char*>(ws);
+  if (!aligned16(logp) || !aligned16(mu_logp) || !aligned16(coef) || !aligned16(adv) || !aligned16(targets) ||
+      (reinterpret_cast<uintptr_t>(mask) & 3u) != 0)
+    return fail(LLAMARL_ERR_INVALID_ARG, "logp, mu_logp, adv, targets and coef must be 16-byte aligned, mask 4-byte");
+  return LLAMARL_OK;
+}
+
+// the two launches of the loss forward; wsb holds a LossWs layout for (B*T, B)
+static llamarl_status launch_loss_fwd(const float* logp, const float* mu_logp, const float* adv, int adv_per_token,
+                                      const uint8_t* mask, const int32_t* targets, int64_t V, int64_t B, int64_t T,
+                                      const llamarl_loss_params* p, float* loss, float* coef, float* stats, char* wsb,
+                                      const LossWs& w, hipStream_t st) {
   LossArgs a;
   a.logp = logp; a.mu_logp = mu_logp; a.adv = adv; a.mask = mask; a.targets = targets; a.V = V; a.B = B; a.T = T;
   a.adv_per_token = adv_per_token; a.rho = p->rho; a.clip_mode = p->clip_mode; a.eps_lo = p->eps_lo;
@@ -352,14 +364,27 @@ llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_log
   a.seq_len = reinterpret_cast<int32_t*>(wsb + w.off_len);
   a.seq_bad = reinterpret_cast<int32_t*>(wsb + w.off_bad);
   a.partials = reinterpret_cast<double*>(wsb + w.off_part);
+  a.ticket = reinterpret_cast<unsigned int*>(wsb + w.off_ticket);
   a.nblocks = w.nblocks; a.coef = coef; a.loss = loss; a.stats = stats;
-  k_seq_lengths<<<dim3((unsigned)B), dim3(LOSS_THREADS), 0, st>>>(a);
+  k_seq_lengths<<<dim3((unsigned)B), dim3(SEQ_THREADS), 0, st>>>(a);          // also clears the ticket
   HIP_TRY(hipGetLastError());
-  k_loss_tokens<<<dim3((unsigned)w.nblocks), dim3(LOSS_THREADS), 0, st>>>(a);
-  HIP_TRY(hipGetLastError());
-  k_loss_finish<<<dim3(1), dim3(LOSS_THREADS), 0, st>>>(a);
+  k_loss_tokens<<<dim3((unsigned)w.nblocks), dim3(LOSS_THREADS), 0, st>>>(a);   // its last block writes loss, stats
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
+}
+
+llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_logp, const float* adv,
+                                          int adv_per_token, const uint8_t* mask, const int32_t* targets, int64_t V,
+                                          int64_t B, int64_t T, const llamarl_loss_params* p, float* loss,
+                                          float* coef, float* stats, void* ws, size_t ws_bytes, void* stream) {
+  llamarl_status s = check_loss_args(logp, mu_logp, adv, mask, targets, V, B, T, p, loss, coef, stats);
+  if (s != LLAMARL_OK) return s;
+  const LossWs w = loss_ws(B * T, B);
+  if (!ws || ws_bytes < w.total)
+    return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, w.total);
+  if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  return launch_loss_fwd(logp, mu_logp, adv, adv_per_token, mask, targets, V, B, T, p, loss, coef, stats,
+                         reinterpret_cast<char*>(ws), w, reinterpret_cast<hipStream_t>(stream));
 }
 
 static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* targets, const float* lse,
@@ -404,6 +429,17 @@ llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, c
     if (!phase_events[i]) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events[%d] is null", i);
   return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes, stream,
                    phase_events);
+}
+
+llamarl_status llamarl_mfma_ceiling(int iters, float* sink, double* flops, void* stream) {
+  if (!sink || !flops) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  if (iters <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "iters must be positive");
+  const int grid = persistent_grid((int64_t)1 << 30);      // one workgroup per CU
+  k_mfma_ceiling<<<dim3((unsigned)grid), dim3(NTHREADS), 0, reinterpret_cast<hipStream_t>(stream)>>>(iters, sink);
+  HIP_TRY(hipGetLastError());
+  // 16x16x32 MFMA = 2 * 16 * 16 * 32 flop; MB x NB of them per k-step and wavefront
+  *flops = (double)grid * (NTHREADS / 64) * (double)iters * CEILING_KSTEPS_PER_ITER * (MB * NB) * (2.0 * 16 * 16 * 32);
+  return LLAMARL_OK;
 }
 
 llamarl_status llamarl_group_advantages(const float* rewards, int64_t P, int64_t n, int normalise_std, float eps,

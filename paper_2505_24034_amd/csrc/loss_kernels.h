@@ -1,7 +1,8 @@
 // loss_kernels.h -- the streaming part of the path: importance ratio, clip, advantage weighting and the
 // masked sequence / batch means (paper Sec. 6 display equation; App. A for the PPO mode).
-// HBM-bound: ~21 bytes per token in, 4 out.  Reductions use wavefront shuffles, then one fixed-order
-// cross-block pass in fp64, so results are bitwise reproducible.
+// HBM-bound: ~21 bytes per token in, 4 out.  Two launches: per-generation lengths, then the tokens.  Reductions
+// use wavefront shuffles, then one fixed-order cross-block sum in fp64 (run by whichever block finishes last), so
+// results are bitwise reproducible.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -11,6 +12,7 @@ namespace llamarl {
 constexpr int LOSS_THREADS = 256;
 constexpr int LOSS_ITEMS = 4;                                 // tokens per thread
 constexpr int LOSS_BLOCK_TOKENS = LOSS_THREADS * LOSS_ITEMS;  // 1024
+constexpr int LOSS_MAX_BLOCKS = 512;                          // k_loss_tokens strides over the batch beyond this
 constexpr int LOSS_NSUM = 5;                                  // loss, sum r, clipped count, sum delta, valid count
 
 struct LossArgs {
@@ -30,6 +32,7 @@ struct LossArgs {
   int32_t* seq_bad;    // [B] unmasked tokens with an out-of-range target
   double* partials;    // [nblocks][LOSS_NSUM]
   int nblocks;
+  unsigned int* ticket;  // blocks of k_loss_tokens that have stored their partials (zeroed by k_seq_lengths)
   float* coef;
   float* loss;
   float* stats;
@@ -54,17 +57,18 @@ __device__ __forceinline__ V wave_sum(V v) {
 }
 
 // one block per generation: valid-token count and bad-target count
-__global__ __launch_bounds__(LOSS_THREADS) void k_seq_lengths(LossArgs a) {
+constexpr int SEQ_THREADS = 1024;
+__global__ __launch_bounds__(SEQ_THREADS) void k_seq_lengths(LossArgs a) {
   const int b = blockIdx.x;
   int cnt = 0, nbad = 0;
-  for (int64_t t = threadIdx.x; t < a.T; t += LOSS_THREADS) {
+  for (int64_t t = threadIdx.x; t < a.T; t += SEQ_THREADS) {
     bool bad;
     cnt += token_valid(a, (int64_t)b * a.T + t, &bad) ? 1 : 0;
     nbad += bad ? 1 : 0;
   }
   cnt = wave_sum(cnt);
   nbad = wave_sum(nbad);
-  __shared__ int s_c[LOSS_THREADS / 64], s_b[LOSS_THREADS / 64];
+  __shared__ int s_c[SEQ_THREADS / 64], s_b[SEQ_THREADS / 64];
   if ((threadIdx.x & 63) == 0) {
     s_c[threadIdx.x >> 6] = cnt;
     s_b[threadIdx.x >> 6] = nbad;
@@ -72,19 +76,22 @@ __global__ __launch_bounds__(LOSS_THREADS) void k_seq_lengths(LossArgs a) {
   __syncthreads();
   if (threadIdx.x == 0) {
     int c = 0, d = 0;
-    for (int w = 0; w < LOSS_THREADS / 64; ++w) {
+    for (int w = 0; w < SEQ_THREADS / 64; ++w) {
       c += s_c[w];
       d += s_b[w];
     }
     a.seq_len[b] = c;
     a.seq_bad[b] = d;
+    if (b == 0) *a.ticket = 0u;
   }
 }
 
-// coef[t] and per-block partial sums
+// coef[t] and per-block partial sums; the block that finishes last adds the partials up in a fixed order (by
+// block index, whichever block it is), so loss and statistics are bitwise reproducible without a third launch.
 __global__ __launch_bounds__(LOSS_THREADS) void k_loss_tokens(LossArgs a) {
   __shared__ long long s_red[2][LOSS_THREADS / 64];
-  __shared__ double s_sum[LOSS_NSUM][LOSS_THREADS / 64];
+  __shared__ double s_sum[LOSS_NSUM + 1][LOSS_THREADS / 64];
+  __shared__ bool s_last;
   // every block re-derives the batch normaliser from the B per-generation counts (B is small)
   long long nv = 0, bv = 0;
   for (int64_t b = threadIdx.x; b < a.B; b += LOSS_THREADS) {
@@ -108,28 +115,72 @@ __global__ __launch_bounds__(LOSS_THREADS) void k_loss_tokens(LossArgs a) {
   const float n_valid = (float)(nv > 0 ? nv : 1);
   const float b_valid = (float)(bv > 0 ? bv : 1);
 
+  // a thread owns LOSS_ITEMS consecutive tokens: 16-byte loads of logp, mu_logp, targets (and of a per-token
+  // advantage), 4 bytes of mask, one 16-byte store of coef -- every array starts 16-byte aligned and t0 is a
+  // multiple of LOSS_ITEMS.  The last, partial group of the batch goes token by token.
+  static_assert(LOSS_ITEMS == 4, "vector width of the token loop");
   double acc[LOSS_NSUM] = {0, 0, 0, 0, 0};
   const int64_t N = a.B * a.T;
-  const int64_t base = (int64_t)blockIdx.x * LOSS_BLOCK_TOKENS;
+  for (int64_t chunk = blockIdx.x; chunk * LOSS_BLOCK_TOKENS < N; chunk += gridDim.x) {
+    const int64_t t0 = chunk * LOSS_BLOCK_TOKENS + (int64_t)threadIdx.x * LOSS_ITEMS;
+    if (t0 >= N) break;
+    const bool whole = t0 + LOSS_ITEMS <= N;
+    float lp4[4], mu4[4], ad4[4];
+    int tg4[4];
+    uint8_t mk4[4];
+    if (whole) {
+      const float4 l = *reinterpret_cast<const float4*>(a.logp + t0);
+      const float4 m = *reinterpret_cast<const float4*>(a.mu_logp + t0);
+      lp4[0] = l.x; lp4[1] = l.y; lp4[2] = l.z; lp4[3] = l.w;
+      mu4[0] = m.x; mu4[1] = m.y; mu4[2] = m.z; mu4[3] = m.w;
+      if (a.mask != nullptr) {
+        const uchar4 k = *reinterpret_cast<const uchar4*>(a.mask + t0);
+        mk4[0] = k.x; mk4[1] = k.y; mk4[2] = k.z; mk4[3] = k.w;
+      }
+      if (a.targets != nullptr) {
+        const int4 y = *reinterpret_cast<const int4*>(a.targets + t0);
+        tg4[0] = y.x; tg4[1] = y.y; tg4[2] = y.z; tg4[3] = y.w;
+      }
+      if (a.adv_per_token) {
+        const float4 v = *reinterpret_cast<const float4*>(a.adv + t0);
+        ad4[0] = v.x; ad4[1] = v.y; ad4[2] = v.z; ad4[3] = v.w;
+      }
+    } else {
 #pragma unroll
-  for (int it = 0; it < LOSS_ITEMS; ++it) {
-    const int64_t t = base + it * LOSS_THREADS + threadIdx.x;
-    if (t >= N) continue;
-    bool bad;
-    const bool valid = token_valid(a, t, &bad);
-    float c = 0.f;
-    if (valid) {
-      const int64_t b = t / a.T;
-      const float lp = a.logp[t];
-      const float delta = lp - a.mu_logp[t];
+      for (int i = 0; i < LOSS_ITEMS; ++i) {
+        const int64_t t = min(t0 + i, N - 1);
+        lp4[i] = a.logp[t];
+        mu4[i] = a.mu_logp[t];
+        mk4[i] = a.mask != nullptr ? a.mask[t] : (uint8_t)1;
+        tg4[i] = a.targets != nullptr ? a.targets[t] : 0;
+        ad4[i] = a.adv_per_token ? a.adv[t] : 0.f;
+      }
+    }
+    int64_t b = t0 / a.T;                         // generation of the first token; later ones step over the edge
+    int64_t in_b = t0 - b * a.T;
+    float c4[4];
+#pragma unroll
+    for (int i = 0; i < LOSS_ITEMS; ++i) {
+      while (in_b >= a.T) {
+        in_b -= a.T;
+        ++b;
+      }
+      ++in_b;
+      c4[i] = 0.f;
+      if (t0 + i >= N) continue;
+      const bool m = (a.mask == nullptr) || (mk4[i] != 0);
+      const bool bad = m && a.targets != nullptr && (tg4[i] < 0 || (int64_t)tg4[i] >= a.V);
+      if (!m || bad) continue;
+      const float lp = lp4[i];
+      const float delta = lp - mu4[i];
       const float r = expf(delta);
-      const float A = a.adv_per_token ? a.adv[t] : a.adv[b];
+      const float A = a.adv_per_token ? ad4[i] : a.adv[b];
       float Z;
       if (a.norm_mode == 0) Z = n_valid;
       else if (a.norm_mode == 1) Z = b_valid * (float)max(a.seq_len[b], 1);
       else Z = (float)a.B;
       bool clipped;
-      float term;
+      float term, c;
       if (a.clip_mode == 0) {
         const float w = fminf(r, a.rho);          // one-sided clip from above; w is a constant weight
         c = -(w * A) / Z;
@@ -143,13 +194,20 @@ __global__ __launch_bounds__(LOSS_THREADS) void k_loss_tokens(LossArgs a) {
         clipped = !active;
         term = -fminf(u, k) / Z;
       }
+      c4[i] = c;
       acc[0] += (double)term;
       acc[1] += (double)r;
       acc[2] += clipped ? 1.0 : 0.0;
       acc[3] += (double)delta;
       acc[4] += 1.0;
     }
-    a.coef[t] = c;
+    if (whole) {
+      *reinterpret_cast<float4*>(a.coef + t0) = make_float4(c4[0], c4[1], c4[2], c4[3]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < LOSS_ITEMS; ++i)
+        if (t0 + i < N) a.coef[t0 + i] = c4[i];
+    }
   }
 #pragma unroll
   for (int q = 0; q < LOSS_NSUM; ++q) {
@@ -162,19 +220,27 @@ __global__ __launch_bounds__(LOSS_THREADS) void k_loss_tokens(LossArgs a) {
     for (int w = 0; w < LOSS_THREADS / 64; ++w) v += s_sum[threadIdx.x][w];
     a.partials[(int64_t)blockIdx.x * LOSS_NSUM + threadIdx.x] = v;
   }
-}
+  // publish the partials, then take a ticket: the block that draws the last one sees everybody's.  The fence
+  // makes this chip's per-XCD L2 write its dirty lines back, which is slow: one wavefront per block (the one that
+  // wrote the partials) runs it, and the grid is bounded (LOSS_MAX_BLOCKS) whatever the batch size.
+  if (threadIdx.x < 64) {
+    __threadfence();
+    if (threadIdx.x == 0) s_last = atomicAdd(a.ticket, 1u) == (unsigned int)a.nblocks - 1u;
+  }
+  __syncthreads();
+  if (!s_last) return;                            // block-uniform
+  if (threadIdx.x < 64) __threadfence();
+  __syncthreads();
 
-// one block: fixed-order sum of the block partials -> loss, stats
-__global__ __launch_bounds__(LOSS_THREADS) void k_loss_finish(LossArgs a) {
-  __shared__ double s_sum[LOSS_NSUM + 1][LOSS_THREADS / 64];
-  double acc[LOSS_NSUM + 1] = {0, 0, 0, 0, 0, 0};
+  double tot[LOSS_NSUM + 1] = {0, 0, 0, 0, 0, 0};
   for (int i = threadIdx.x; i < a.nblocks; i += LOSS_THREADS)
 #pragma unroll
-    for (int q = 0; q < LOSS_NSUM; ++q) acc[q] += a.partials[(int64_t)i * LOSS_NSUM + q];
-  for (int64_t b = threadIdx.x; b < a.B; b += LOSS_THREADS) acc[LOSS_NSUM] += (double)a.seq_bad[b];
+    for (int q = 0; q < LOSS_NSUM; ++q)           // device-scope loads: other CUs wrote these during this launch
+      tot[q] += __hip_atomic_load(a.partials + (int64_t)i * LOSS_NSUM + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int64_t b = threadIdx.x; b < a.B; b += LOSS_THREADS) tot[LOSS_NSUM] += (double)a.seq_bad[b];
 #pragma unroll
   for (int q = 0; q <= LOSS_NSUM; ++q) {
-    const double v = wave_sum(acc[q]);
+    const double v = wave_sum(tot[q]);
     if ((threadIdx.x & 63) == 0) s_sum[q][threadIdx.x >> 6] = v;
   }
   __syncthreads();
