@@ -138,6 +138,22 @@ llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_log
                                           float* coef, float* stats, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * llamarl_offpolicy_loss_fwd for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without `ws`, same kernels, same
+ * results bit for bit; the kernels' scratch (per-generation counters, per-block partial sums, a ticket: about
+ * 0.5 MB) is a static device array inside the library, one copy per GPU, held until the process ends.
+ *   - limits: B <= 65536 generations and B*T <= 4194304 tokens, LLAMARL_ERR_UNSUPPORTED beyond them;
+ *   - allocates nothing (no hipMalloc / hipFree, no allocating library routine), clears what it needs with its
+ *     own kernels (no memset node in a captured graph);
+ *   - every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads) race.
+ *     Calls on one stream, or ordered by events, are fine.  It works on the current device.
+ */
+llamarl_status llamarl_offpolicy_loss_fwd_static(const float* logp, const float* mu_logp, const float* adv,
+                                                 int adv_per_token, const uint8_t* mask, const int32_t* targets,
+                                                 int64_t V, int64_t B, int64_t T, const llamarl_loss_params* p,
+                                                 float* loss, float* coef, float* stats, void* stream);
+
+/*
  * Backward of the loss through logp[t] = z[t,y_t] - lse[t] (chain rule on the
  * Sec. 6 update, which is a weighted sum of grad log pi(y_t|.)).  Logits are
  * recomputed tile by tile:

@@ -21,7 +21,8 @@ PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
            "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
-           "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling")
+           "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling",
+           "llamarl_offpolicy_loss_fwd_static")
 
 
 class LlamarlError(RuntimeError):
@@ -58,6 +59,9 @@ def load():
     lib.llamarl_offpolicy_loss_fwd.restype = ci
     lib.llamarl_offpolicy_loss_fwd.argtypes = [vp, vp, vp, ci, vp, vp, i64, i64, i64, ctypes.POINTER(LossParams),
                                                vp, vp, vp, vp, sz, vp]
+    lib.llamarl_offpolicy_loss_fwd_static.restype = ci
+    lib.llamarl_offpolicy_loss_fwd_static.argtypes = [vp, vp, vp, ci, vp, vp, i64, i64, i64,
+                                                      ctypes.POINTER(LossParams), vp, vp, vp, vp]
     lib.llamarl_offpolicy_loss_bwd.restype = ci
     lib.llamarl_offpolicy_loss_bwd.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, ci, vp, vp, ci, ci, vp, sz, vp]
     lib.llamarl_offpolicy_loss_bwd_phases.restype = ci
@@ -156,6 +160,32 @@ def offpolicy_loss_fwd(logp, mu_logp, adv, mask, B, T, rho=2.0, norm_mode=NORM_T
     _check(lib.llamarl_offpolicy_loss_fwd(_ptr(logp), _ptr(mu_logp), _ptr(adv), per_token, _ptr(mask), _ptr(targets),
                                           int(V), B, T, ctypes.byref(p), _ptr(loss), _ptr(coef), _ptr(stats),
                                           _ptr(ws), ws.numel(), _stream(stream)))
+    return loss, coef, stats
+
+
+def offpolicy_loss_fwd_static(logp, mu_logp, adv, mask, B, T, loss, coef, stats, rho=2.0, norm_mode=NORM_TOKEN_MEAN,
+                              clip_mode=CLIP_AIPO, eps_lo=0.2, eps_hi=0.2, targets=None, V=0, stream=None):
+    """llamarl_offpolicy_loss_fwd_static: the caller passes every buffer (loss [1], coef [B*T], stats [5]); the
+    call allocates nothing and uses the library's static device scratch."""
+    lib = load()
+    N = B * T
+    for t, n, name in ((logp, N, "logp"), (mu_logp, N, "mu_logp"), (coef, N, "coef"), (loss, 1, "loss"),
+                       (stats, 5, "stats")):
+        _need(t, torch.float32, name)
+        if t.numel() != n:
+            raise LlamarlError(ERR_INVALID_ARG, "%s must have %d entries" % (name, n))
+    _need(adv, torch.float32, "adv")
+    if adv.numel() not in (B, N):
+        raise LlamarlError(ERR_INVALID_ARG, "adv must have B or B*T entries")
+    per_token = 1 if (adv.numel() == N and N != B) else 0
+    if mask is not None:
+        _need(mask, torch.uint8, "mask")
+    if targets is not None:
+        _need(targets, torch.int32, "targets")
+    p = LossParams(float(rho), int(clip_mode), float(eps_lo), float(eps_hi), int(norm_mode))
+    _check(lib.llamarl_offpolicy_loss_fwd_static(_ptr(logp), _ptr(mu_logp), _ptr(adv), per_token, _ptr(mask),
+                                                 _ptr(targets), int(V), B, T, ctypes.byref(p), _ptr(loss),
+                                                 _ptr(coef), _ptr(stats), _stream(stream)))
     return loss, coef, stats
 
 

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "ceiling_kernel.h"
 #include "head_kernels.h"
@@ -68,6 +69,20 @@ LossWs loss_ws(int64_t N, int64_t B) {  // B generations, N = B * T tokens
   return w;
 }
 
+
+// Scratch of llamarl_offpolicy_loss_fwd_static: room for the LossWs layout at the entry point's stated maximum
+// (2 x 65536 per-generation counters, LOSS_MAX_BLOCKS x LOSS_NSUM partial sums, the ticket): about 0.5 MB that every
+// GPU the library runs on holds until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress(); kernels get the device address that call returns.
+constexpr int64_t STATIC_MAX_TOKENS = (int64_t)1 << 22;
+constexpr int64_t STATIC_MAX_GENERATIONS = (int64_t)1 << 16;
+constexpr size_t STATIC_SCRATCH_BYTES =
+    2 * (size_t)STATIC_MAX_GENERATIONS * 4 + ((size_t)LOSS_MAX_BLOCKS * LOSS_NSUM * 8 + 255) / 256 * 256 + 256;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[STATIC_MAX_DEVICES] = {};      // device address of `scratch` on each GPU, looked up once
 
 struct BwdWs {
   int64_t ldz, ldzt;  // padded leading dimensions (elements): V and N rounded up to 64
@@ -385,6 +400,43 @@ llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_log
   if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
   return launch_loss_fwd(logp, mu_logp, adv, adv_per_token, mask, targets, V, B, T, p, loss, coef, stats,
                          reinterpret_cast<char*>(ws), w, reinterpret_cast<hipStream_t>(stream));
+}
+
+// Device address of this GPU's copy of `scratch` (each GPU has its own, at its own address).
+static llamarl_status scratch_of_current_device(char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(LLAMARL_ERR_UNSUPPORTED, "device ordinal %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return fail(LLAMARL_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<char*>(g_scratch_ptr[dev]);
+  return LLAMARL_OK;
+}
+
+llamarl_status llamarl_offpolicy_loss_fwd_static(const float* logp, const float* mu_logp, const float* adv,
+                                                 int adv_per_token, const uint8_t* mask, const int32_t* targets,
+                                                 int64_t V, int64_t B, int64_t T, const llamarl_loss_params* p,
+                                                 float* loss, float* coef, float* stats, void* stream) {
+  llamarl_status s = check_loss_args(logp, mu_logp, adv, mask, targets, V, B, T, p, loss, coef, stats);
+  if (s != LLAMARL_OK) return s;
+  if (B > STATIC_MAX_GENERATIONS || B * T > STATIC_MAX_TOKENS)
+    return fail(LLAMARL_ERR_UNSUPPORTED,
+                "B = %lld, B*T = %lld exceed the static scratch of this entry point (at most %lld generations, %lld "
+                "tokens): use llamarl_offpolicy_loss_fwd with a workspace",
+                (long long)B, (long long)(B * T), (long long)STATIC_MAX_GENERATIONS, (long long)STATIC_MAX_TOKENS);
+  const LossWs w = loss_ws(B * T, B);
+  if (w.total > STATIC_SCRATCH_BYTES) return fail(LLAMARL_ERR_UNSUPPORTED, "static scratch too small for this batch");
+  char* base = nullptr;
+  s = scratch_of_current_device(&base);
+  if (s != LLAMARL_OK) return s;
+  // nothing in the scratch has to start at zero: k_seq_lengths overwrites the counters and clears the ticket
+  return launch_loss_fwd(logp, mu_logp, adv, adv_per_token, mask, targets, V, B, T, p, loss, coef, stats, base, w,
+                         reinterpret_cast<hipStream_t>(stream));
 }
 
 static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* targets, const float* lse,
