@@ -221,6 +221,77 @@ def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0):
     return dH, dW
 
 
+def token_logprobs_partial(H, W_slice, targets, v0, V_total, mask=None):
+    """What one shard of a vocabulary-parallel head contributes (Sec. 8.2, Table 3: the trainer runs with model
+    parallelism 8-32, so each device holds the rows [v0, v0 + V_slice) of the head weight): for every token the
+    maximum m of its slice of the logits, s = sum over the slice of exp(z - m), and the target's logit zt if
+    the target lies in the slice (0 otherwise).  Rows that are masked, or whose target is outside [0, V_total),
+    return (m, s, zt) = (-inf, 0, 0).  Returns (m [N], s [N], zt [N])."""
+    Hd, Wd = widen(H), widen(W_slice)
+    N, Vs = Hd.shape[0], Wd.shape[0]
+    targets = np.asarray(targets).astype(np.int64).reshape(N)
+    valid = np.ones(N, dtype=bool) if mask is None else (np.asarray(mask).reshape(N) != 0)
+    valid = valid & (targets >= 0) & (targets < int(V_total))
+    m = np.full(N, -np.inf)
+    s = np.zeros(N)
+    zt = np.zeros(N)
+    rows = np.nonzero(valid)[0]
+    if rows.size:
+        Z = Hd[rows] @ Wd.T
+        mr = Z.max(axis=1)
+        m[rows] = mr
+        s[rows] = np.exp(Z - mr[:, None]).sum(axis=1)
+        local = targets[rows] - int(v0)
+        own = (local >= 0) & (local < Vs)
+        zt[rows[own]] = Z[np.nonzero(own)[0], local[own]]
+    return m, s, zt
+
+
+def merge_partials(m_parts, s_parts, zt_parts):
+    """Combine the shards' (m, s, zt) [p, N] into lse and logp: the quantities a vocabulary-parallel head would
+    all-reduce (max for m, a rescaled sum for s, a plain sum for zt -- exactly one shard holds the target).
+        M = max_p m_p,  lse = M + log sum_p s_p exp(m_p - M),  logp = sum_p zt_p - lse
+    Rows whose every m_p is -inf (masked / bad target) return logp = lse = 0."""
+    m = np.asarray(m_parts, dtype=np.float64)
+    s = np.asarray(s_parts, dtype=np.float64)
+    zt = np.asarray(zt_parts, dtype=np.float64)
+    M = m.max(axis=0)
+    live = np.isfinite(M)
+    Ms = np.where(live, M, 0.0)
+    with np.errstate(invalid="ignore"):
+        S = np.where(np.isfinite(m), s * np.exp(m - Ms[None, :]), 0.0).sum(axis=0)
+    lse = np.where(live, Ms + np.log(np.where(live, S, 1.0)), 0.0)
+    logp = np.where(live, zt.sum(axis=0) - lse, 0.0)
+    return logp, lse
+
+
+def offpolicy_loss_bwd_slice(H, W_slice, targets, v0, lse, coef, grad_loss=1.0):
+    """A shard's part of the backward: with the GLOBAL lse (from merge_partials) the slice of dz is
+        dz[t,v] = grad_loss * coef_t * (1[v0 + v = y_t] - exp(z[t,v] - lse_t)),   v in the slice,
+    its head-weight gradient is that shard's rows of dW, and dH_partial = dz @ W_slice is the shard's summand of
+    dH (the shards' dH_partial add up to dH: the reduce-scatter of a vocabulary-parallel head).
+    Returns (dH_partial [N,d], dW_slice [V_slice,d])."""
+    Hd, Wd = widen(H), widen(W_slice)
+    N, d = Hd.shape
+    Vs = Wd.shape[0]
+    targets = np.asarray(targets).astype(np.int64).reshape(N)
+    lse = np.asarray(lse, dtype=np.float64).reshape(N)
+    dlogp = float(grad_loss) * np.asarray(coef, dtype=np.float64).reshape(N)
+    dH = np.zeros((N, d), dtype=np.float64)
+    dW = np.zeros((Vs, d), dtype=np.float64)
+    rows = np.nonzero(dlogp != 0.0)[0]
+    if rows.size:
+        Hr = Hd[rows]
+        dZ = -np.exp(Hr @ Wd.T - lse[rows][:, None])
+        local = targets[rows] - int(v0)
+        own = (local >= 0) & (local < Vs)
+        dZ[np.nonzero(own)[0], local[own]] += 1.0
+        dZ *= dlogp[rows][:, None]
+        dH[rows] = dZ @ Wd
+        dW = dZ.T @ Hr
+    return dH, dW
+
+
 def group_advantages(rewards, n, normalise_std=False, eps=1e-6):
     """Group-mean baseline (Sec. 6): from one prompt n generations are sampled and the baseline is the mean of
     their rewards, constant over a generation's tokens: A_i = r_i - (1/n) sum_j r_j.  With normalise_std the

@@ -596,3 +596,68 @@ def test_kl_shaped_rewards_special_cases():
     # a policy more confident than the base on its own samples is penalised (sign of the term)
     s, kl = orc.kl_shaped_rewards(np.zeros(1), np.full((1, 4), -0.1), np.full((1, 4), -2.0), np.ones((1, 4)), 1.0)
     assert kl[0] > 0 and s[0] < 0
+
+
+# ---------------------------------------------------------------- vocabulary-sliced head (Sec. 8.2: trainer mp 8-32)
+def _slices(V, p):
+    edges = [round(i * V / p) for i in range(p + 1)]
+    return [(edges[i], edges[i + 1]) for i in range(p) if edges[i + 1] > edges[i]]
+
+
+@pytest.mark.parametrize("p", [1, 2, 3, 4])
+def test_sliced_forward_merges_to_the_unsliced_log_probs(p):
+    H, W, tg, mu, adv, mask = _rand_problem(41, B=3, T=6, d=7, V=13)
+    H[:, 0] += 3.0                                   # uneven slice maxima
+    tg[4] = 13                                       # out of range: the row is dead in every shard
+    mflat = mask.reshape(-1)
+    ref_logp, ref_lse = orc.token_logprobs(H, W, tg, mflat)
+    parts = [orc.token_logprobs_partial(H, W[a:b], tg, a, W.shape[0], mflat) for a, b in _slices(W.shape[0], p)]
+    m, s, zt = (np.stack([q[i] for q in parts]) for i in range(3))
+    logp, lse = orc.merge_partials(m, s, zt)
+    assert np.allclose(logp, ref_logp, rtol=1e-13, atol=1e-13) and np.allclose(lse, ref_lse, rtol=1e-13, atol=1e-13)
+    dead = (mflat == 0) | (tg < 0) | (tg >= W.shape[0])
+    assert dead.any() and not logp[dead].any() and not lse[dead].any()
+    assert np.all(np.isneginf(m[:, dead])) and not s[:, dead].any() and not zt[:, dead].any()
+
+
+def test_slice_partials_are_the_slice_logsumexp_and_the_target_logit():
+    # each shard's (m, s) is its own logsumexp (library routine on loop logits), zt the one logit the shard owns
+    H, W, tg, mu, adv, mask = _rand_problem(42, B=2, T=5, d=6, V=10)
+    a, b = 3, 8
+    m, s, zt = orc.token_logprobs_partial(H, W[a:b], tg, a, W.shape[0])
+    for t in range(H.shape[0]):
+        z = [sum(H[t, k] * W[v, k] for k in range(H.shape[1])) for v in range(a, b)]
+        assert m[t] == pytest.approx(max(z), rel=1e-14)
+        assert m[t] + math.log(s[t]) == pytest.approx(scipy.special.logsumexp(z), rel=1e-13)
+        assert zt[t] == pytest.approx(z[tg[t] - a] if a <= tg[t] < b else 0.0, rel=1e-13, abs=0)
+    # shifting every logit of a shard by kappa shifts its m by kappa and leaves s alone (ones column trick)
+    H1 = np.concatenate([H, np.ones((H.shape[0], 1))], axis=1)
+    W1 = np.concatenate([W, np.full((W.shape[0], 1), 40.0)], axis=1)
+    m2, s2, _ = orc.token_logprobs_partial(H1, W1[a:b], tg, a, W.shape[0])
+    assert np.allclose(m2, m + 40.0, rtol=1e-14) and np.allclose(s2, s, rtol=1e-12)
+
+
+@pytest.mark.parametrize("p", [2, 4])
+def test_sliced_backward_adds_up_to_the_unsliced_gradients(p):
+    H, W, tg, mu, adv, mask = _rand_problem(43, B=3, T=5, d=6, V=11)
+    out = orc.aipo_step(H, W, tg, mu, adv, mask, 1.3, grad_loss=-0.7)
+    dH = np.zeros_like(out["dH"])
+    dW_rows = []
+    for a, b in _slices(W.shape[0], p):
+        gH, gW = orc.offpolicy_loss_bwd_slice(H, W[a:b], tg, a, out["lse"], out["coef"], -0.7)
+        dH += gH
+        dW_rows.append(gW)
+    assert np.allclose(dH, out["dH"], rtol=1e-12, atol=1e-15)
+    assert np.allclose(np.concatenate(dW_rows), out["dW"], rtol=1e-12, atol=1e-15)
+    # the shard that does not own a token's target still gets -p * coef for it: its dW rows are not zero
+    assert all(np.abs(g).max() > 0 for g in dW_rows)
+
+
+def test_sliced_backward_matches_torch_autograd_of_the_full_loss_restricted_to_the_slice():
+    # independent of the unsliced oracle backward: autograd of the detached-weight loss w.r.t. the FULL W, rows a:b
+    H, W, tg, mu, adv, mask = _rand_problem(44, B=2, T=6, d=5, V=9)
+    out = orc.aipo_step(H, W, tg, mu, adv, mask, 1.5)
+    loss, gH, gW = _torch_loss(H, W, tg, mu, adv, mask, 1.5, orc.NORM_TOKEN_MEAN)
+    a, b = 2, 7
+    _, gWs = orc.offpolicy_loss_bwd_slice(H, W[a:b], tg, a, out["lse"], out["coef"])
+    assert np.allclose(gWs, gW[a:b], rtol=1e-10, atol=1e-14)
