@@ -178,6 +178,40 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Vocabulary-sharded head (Sec. 8.2, Table 3: the trainer runs with model parallelism 8-32, i.e. every device
+ * holds a slice of the head's vocabulary rows).  These three calls are one shard's share of the path; the exchange
+ * between shards (an all-reduce of 12 bytes per token, a reduce-scatter of dH) is the caller's.  On one GPU the
+ * shards can be run one after another.
+ *
+ * llamarl_token_logprobs_partial: W_slice holds rows [v0, v0 + V_slice) of a head with V_total rows; targets are
+ * global vocabulary indices.  Per token, over the shard's logits z:
+ *     m[t] = max_v z[t,v]     s[t] = sum_v exp(z[t,v] - m[t])     zt[t] = z[t, y_t] if v0 <= y_t < v0 + V_slice else 0
+ * Rows with mask == 0 or a target outside [0, V_total) get (m, s, zt) = (-inf, 0, 0).
+ *   m, s, zt  out float [N];  ws >= llamarl_workspace_bytes(N, d, V_slice, dt, LLAMARL_PASS_LOGPROBS)
+ *
+ * llamarl_merge_partials: what the all-reduce computes, for `shards` results stored shard-major ([shards][N]):
+ *     M = max_p m_p    lse = M + log sum_p s_p exp(m_p - M)    logp = sum_p zt_p - lse
+ * (rows dead in every shard: logp = lse = 0).  With shards = 1 it finishes a single partial call.
+ *
+ * llamarl_offpolicy_loss_bwd_slice: llamarl_offpolicy_loss_bwd for the shard.  lse is the GLOBAL log-sum-exp
+ * (from llamarl_merge_partials), so dz[t,v] = grad_loss * coef[t] * (1[v0 + v == y_t] - exp(z[t,v] - lse[t]))
+ * is the shard's slice of the full dz;  dW_slice [V_slice,d] = dz^T H is the shard's rows of dW, and
+ * dH_partial [N,d] = dz W_slice is its summand of dH (the shards' partials add up to dH).
+ *   ws >= llamarl_workspace_bytes(N, d, V_slice, dt, LLAMARL_PASS_LOSS_BWD)
+ */
+llamarl_status llamarl_token_logprobs_partial(const void* H, const void* W_slice, const int32_t* targets,
+                                              const uint8_t* mask, int64_t N, int64_t d, int64_t V_slice, int64_t v0,
+                                              int64_t V_total, llamarl_dtype dt, float* m, float* s, float* zt,
+                                              void* ws, size_t ws_bytes, void* stream);
+llamarl_status llamarl_merge_partials(const float* m, const float* s, const float* zt, int shards, int64_t N,
+                                      float* logp, float* lse, void* stream);
+llamarl_status llamarl_offpolicy_loss_bwd_slice(const void* H, const void* W_slice, const int32_t* targets,
+                                                const float* lse, const float* coef, float grad_loss, int64_t N,
+                                                int64_t d, int64_t V_slice, int64_t v0, llamarl_dtype dt,
+                                                void* dH_partial, void* dW_slice, llamarl_dtype dW_dt,
+                                                int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * MEASUREMENT AID, outside the method: llamarl_offpolicy_loss_bwd, which in addition records six caller-owned HIP events
  * (phase_events[0..5], HOST array of hipEvent_t passed as void*) on `stream`: [0] before the first kernel,
  * [1] after the set-up kernels (active-row list, zeroed dH rows, operand panels), [2] after the recompute + dz

@@ -22,7 +22,8 @@ PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
            "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
            "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling",
-           "llamarl_offpolicy_loss_fwd_static")
+           "llamarl_offpolicy_loss_fwd_static", "llamarl_token_logprobs_partial", "llamarl_merge_partials",
+           "llamarl_offpolicy_loss_bwd_slice")
 
 
 class LlamarlError(RuntimeError):
@@ -71,6 +72,13 @@ def load():
     lib.llamarl_group_advantages.argtypes = [vp, i64, i64, ci, cf, vp, vp]
     lib.llamarl_kl_shaped_rewards.restype = ci
     lib.llamarl_kl_shaped_rewards.argtypes = [vp, vp, vp, vp, i64, i64, cf, vp, vp, vp]
+    lib.llamarl_token_logprobs_partial.restype = ci
+    lib.llamarl_token_logprobs_partial.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp, vp, vp, vp, sz, vp]
+    lib.llamarl_merge_partials.restype = ci
+    lib.llamarl_merge_partials.argtypes = [vp, vp, vp, ci, i64, vp, vp, vp]
+    lib.llamarl_offpolicy_loss_bwd_slice.restype = ci
+    lib.llamarl_offpolicy_loss_bwd_slice.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, i64, ci, vp, vp, ci, ci, vp,
+                                                     sz, vp]
     lib.llamarl_mfma_ceiling.restype = ci
     lib.llamarl_mfma_ceiling.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -261,3 +269,54 @@ def mfma_ceiling(iters, sink, stream=None):
     flops = ctypes.c_double()
     _check(lib.llamarl_mfma_ceiling(int(iters), _ptr(sink), ctypes.byref(flops), _stream(stream)))
     return float(flops.value)
+
+
+def token_logprobs_partial(H, W_slice, targets, v0, V_total, mask=None, ws=None, stream=None):
+    """llamarl_token_logprobs_partial: one vocabulary shard's (m [N], s [N], zt [N])."""
+    lib = load()
+    dt = _dtype_code(H)
+    _need(H, H.dtype, "H"); _need(W_slice, H.dtype, "W_slice"); _need(targets, torch.int32, "targets")
+    N, d = H.shape
+    Vs = W_slice.shape[0]
+    if W_slice.shape[1] != d or targets.numel() != N:
+        raise LlamarlError(ERR_INVALID_ARG, "shape mismatch between H, W_slice, targets")
+    if mask is not None:
+        _need(mask, torch.uint8, "mask")
+    m, s, zt = (torch.empty(N, dtype=torch.float32, device=H.device) for _ in range(3))
+    ws = _workspace(workspace_bytes(N, d, Vs, dt, PASS_LOGPROBS), H.device, ws)
+    _check(lib.llamarl_token_logprobs_partial(_ptr(H), _ptr(W_slice), _ptr(targets), _ptr(mask), N, d, Vs, int(v0),
+                                              int(V_total), dt, _ptr(m), _ptr(s), _ptr(zt), _ptr(ws), ws.numel(),
+                                              _stream(stream)))
+    return m, s, zt
+
+
+def merge_partials(m, s, zt, stream=None):
+    """llamarl_merge_partials: m, s, zt [shards, N] -> (logp [N], lse [N])."""
+    lib = load()
+    for t, name in ((m, "m"), (s, "s"), (zt, "zt")):
+        _need(t, torch.float32, name)
+    if m.dim() != 2 or m.shape != s.shape or m.shape != zt.shape:
+        raise LlamarlError(ERR_INVALID_ARG, "m, s, zt must be [shards, N]")
+    shards, N = m.shape
+    logp = torch.empty(N, dtype=torch.float32, device=m.device)
+    lse = torch.empty(N, dtype=torch.float32, device=m.device)
+    _check(lib.llamarl_merge_partials(_ptr(m), _ptr(s), _ptr(zt), shards, N, _ptr(logp), _ptr(lse), _stream(stream)))
+    return logp, lse
+
+
+def offpolicy_loss_bwd_slice(H, W_slice, targets, v0, lse, coef, grad_loss=1.0, dW_dtype=None, ws=None, stream=None):
+    """llamarl_offpolicy_loss_bwd_slice: returns (dH_partial [N,d], dW_slice [V_slice,d])."""
+    lib = load()
+    dt = _dtype_code(H)
+    _need(H, H.dtype, "H"); _need(W_slice, H.dtype, "W_slice"); _need(targets, torch.int32, "targets")
+    _need(lse, torch.float32, "lse"); _need(coef, torch.float32, "coef")
+    N, d = H.shape
+    Vs = W_slice.shape[0]
+    dW_dtype = dW_dtype or H.dtype
+    dH = torch.empty(N, d, dtype=H.dtype, device=H.device)
+    dW = torch.empty(Vs, d, dtype=dW_dtype, device=H.device)
+    ws = _workspace(workspace_bytes(N, d, Vs, dt, PASS_LOSS_BWD), H.device, ws)
+    _check(lib.llamarl_offpolicy_loss_bwd_slice(_ptr(H), _ptr(W_slice), _ptr(targets), _ptr(lse), _ptr(coef),
+                                                float(grad_loss), N, d, Vs, int(v0), dt, _ptr(dH), _ptr(dW),
+                                                _dtype_code(dW), 0, _ptr(ws), ws.numel(), _stream(stream)))
+    return dH, dW

@@ -67,7 +67,8 @@ struct FwdArgs {
   const void* H;
   const void* W;
   const int32_t* targets;
-  int64_t N, d, V;
+  int64_t N, d, V;        // V: rows of W as passed (the whole vocabulary, or a shard's slice of it)
+  int64_t v_off;          // vocabulary index of row 0 of W (0 unless W is a slice): targets are global indices
   int tiles_v, tiles_t;   // tiles over the vocabulary (MFMA rows) and over the tokens (MFMA columns)
   int64_t n_pad;          // row stride of the partial arrays
   float* part_m;          // [tiles_v][n_pad] max of the tile's logits of a token
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int tok = lp.col(j);
-      const int y = (tok < rowsT) ? ytok[j] : -1;
+      const int y = (tok < rowsT) ? ytok[j] - (int)a.v_off : -1;   // row of W that is the target (negative: none)
       const int yrow = y - (int)v0;                  // vocab row of the target inside this tile (if 0 <= . < rowsV)
       const int yrel = yrow - lane_row0;             // ... relative to this lane's first row
       float m = -INFINITY;
@@ -221,19 +222,33 @@ __global__ __launch_bounds__(NTHREADS) void k_fwd_partials(FwdArgs a) {
 // threads takes 32 list positions x 32 slices of the vocab tiles, so a row of 32 lanes reads one 128-byte line and
 // there are enough loads in flight to stream.
 constexpr int MERGE_TOKENS = 32, MERGE_SLICES = 32;
-__global__ __launch_bounds__(MERGE_TOKENS * MERGE_SLICES) void k_merge_logp(const float* part_m, const float* part_s,
-                                                                            const float* zt, const int32_t* rows,
-                                                                            const int32_t* n_act, int tiles_v,
-                                                                            int64_t n_pad, float* logp, float* lse) {
+struct MergeArgs {
+  const float* part_m;
+  const float* part_s;
+  const float* zt;
+  const int32_t* rows;
+  const int32_t* n_act;
+  int tiles_v;
+  int64_t n_pad;
+  float* out0;            // full vocabulary: logp           shard: m   (max of the shard's logits)
+  float* out1;            //                  lse                   s   (sum of exp(z - m) over the shard)
+  float* out2;            //                  unused                zt  (target logit if the shard owns it, else 0)
+  const int32_t* targets; // shard only
+  int64_t v_off, V;       // shard only: its vocabulary range is [v_off, v_off + V)
+};
+// PARTIAL: W is a shard of a vocabulary-parallel head; the per-token (m, s, zt) are what the shards would
+// all-reduce (paper Sec. 8.2, Table 3: trainer model parallelism 8-32), see k_merge_shards.
+template <bool PARTIAL>
+__global__ __launch_bounds__(MERGE_TOKENS * MERGE_SLICES) void k_merge_logp(MergeArgs a) {
   __shared__ float s_M[MERGE_SLICES][MERGE_TOKENS], s_S[MERGE_SLICES][MERGE_TOKENS];
   const int tok = threadIdx.x % MERGE_TOKENS, sl = threadIdx.x / MERGE_TOKENS;
   const int64_t p = (int64_t)blockIdx.x * MERGE_TOKENS + tok;
-  const int64_t n = *n_act;
+  const int64_t n = *a.n_act;
   if ((int64_t)blockIdx.x * MERGE_TOKENS >= n) return;        // block-uniform
   float M = -INFINITY, S = 0.f;
   if (p < n) {
-    for (int j = sl; j < tiles_v; j += MERGE_SLICES) {
-      const float m = part_m[(int64_t)j * n_pad + p], s = part_s[(int64_t)j * n_pad + p];
+    for (int j = sl; j < a.tiles_v; j += MERGE_SLICES) {
+      const float m = a.part_m[(int64_t)j * a.n_pad + p], s = a.part_s[(int64_t)j * a.n_pad + p];
       if (m > M) {
         S = S * __expf(M - m) + s;      // exp(-inf) = 0 on the first tile
         M = m;
@@ -250,15 +265,49 @@ __global__ __launch_bounds__(MERGE_TOKENS * MERGE_SLICES) void k_merge_logp(cons
     for (int q = 1; q < MERGE_SLICES; ++q) Mx = fmaxf(Mx, s_M[q][tok]);
     float Sx = 0.f;
     for (int q = 0; q < MERGE_SLICES; ++q) Sx += (s_M[q][tok] == -INFINITY) ? 0.f : s_S[q][tok] * expf(s_M[q][tok] - Mx);
-    const float l = Mx + logf(Sx);
-    const int64_t t = rows[p];
-    lse[t] = l;
-    logp[t] = zt[p] - l;
+    const int64_t t = a.rows[p];
+    if constexpr (PARTIAL) {
+      const int64_t y = (int64_t)a.targets[t] - a.v_off;
+      a.out0[t] = Mx;
+      a.out1[t] = Sx;
+      a.out2[t] = (y >= 0 && y < a.V) ? a.zt[p] : 0.f;
+    } else {
+      const float l = Mx + logf(Sx);
+      a.out1[t] = l;
+      a.out0[t] = a.zt[p] - l;
+    }
   }
 }
 
+// The all-reduce of a vocabulary-parallel head, done here for shards that ran one after another on one GPU:
+//   M = max_p m_p,  lse = M + log sum_p s_p exp(m_p - M),  logp = sum_p zt_p - lse        (m, s, zt: [shards][N])
+// Rows whose every m_p is -inf (masked / bad target in every shard) get logp = lse = 0.  Shards are summed in
+// ascending order: deterministic.
+__global__ __launch_bounds__(256) void k_merge_shards(const float* m, const float* s, const float* zt, int shards,
+                                                       int64_t N, float* logp, float* lse) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= N) return;
+  float M = -INFINITY;
+  for (int p = 0; p < shards; ++p) M = fmaxf(M, m[(int64_t)p * N + t]);
+  float l = 0.f, lp = 0.f;
+  if (M != -INFINITY) {
+    float S = 0.f, Z = 0.f;
+    for (int p = 0; p < shards; ++p) {
+      const float mp = m[(int64_t)p * N + t];
+      S += (mp == -INFINITY) ? 0.f : s[(int64_t)p * N + t] * expf(mp - M);
+      Z += zt[(int64_t)p * N + t];
+    }
+    l = M + logf(S);
+    lp = Z - l;
+  }
+  lse[t] = l;
+  logp[t] = lp;
+}
+
 // Active-row list.  mode 0 (forward): row t is active if mask[t] != 0 (mask == nullptr: always) and its target
-// is inside [0,V); inactive rows get logp = lse = 0 here.  mode 1 (backward): active if coef[t] != 0.
+// is inside [0,V); inactive rows get out0 = out1 = 0 (logp, lse) here.  mode 2 (forward of a shard): the same
+// list, inactive rows get (out0, out1, out2) = (-inf, 0, 0), the shard's (m, s, zt).  mode 1 (backward): active
+// if coef[t] != 0.
 // The list is ascending, so every later kernel is deterministic.  Block b owns rows [b, b+1) * COMPACT_BLOCK_ROWS:
 // it first counts the active rows in front of its range by evaluating the predicate over them (5 bytes a row,
 // served by L2 -- cheaper than a second launch or a cross-block wait for the batch sizes of a trainer step), then
@@ -268,15 +317,15 @@ constexpr int COMPACT_BLOCK_ROWS = 4 * COMPACT_THREADS;
 
 __device__ __forceinline__ bool row_active(int mode, const uint8_t* mask, const int32_t* targets, int64_t V,
                                            const float* coef, int64_t t) {
-  if (mode != 0) return coef[t] != 0.f;
+  if (mode == 1) return coef[t] != 0.f;
   const int y = targets[t];
   return (mask == nullptr || mask[t] != 0) && y >= 0 && (int64_t)y < V;
 }
 
 __global__ __launch_bounds__(COMPACT_THREADS) void k_compact_rows(int mode, const uint8_t* mask, const int32_t* targets,
                                                                    int64_t V, const float* coef, int64_t N,
-                                                                   int32_t* rows, int32_t* n_act, float* logp,
-                                                                   float* lse) {
+                                                                   int32_t* rows, int32_t* n_act, float* out0,
+                                                                   float* out1, float* out2) {
   __shared__ int s_wave[COMPACT_THREADS / 64];
   __shared__ int s_base;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -298,9 +347,10 @@ __global__ __launch_bounds__(COMPACT_THREADS) void k_compact_rows(int mode, cons
     bool act = false;
     if (t < N) {
       act = row_active(mode, mask, targets, V, coef, t);
-      if (mode == 0 && !act) {
-        logp[t] = 0.f;
-        lse[t] = 0.f;
+      if (mode != 1 && !act) {
+        out0[t] = (mode == 2) ? -INFINITY : 0.f;
+        out1[t] = 0.f;
+        if (mode == 2) out2[t] = 0.f;
       }
     }
     const unsigned long long b = __ballot(act);
@@ -339,6 +389,7 @@ struct DzArgs {
   const float* coef;
   float g;
   int64_t N, d, V;
+  int64_t v_off;          // vocabulary index of row 0 of W (0 unless W is a shard's slice); lse is always global
   int tiles_v, tiles_t;
   void* dz;     // [N][ldz]  token-major (type of H/W); columns V..ldz-1 written as zero
   int64_t ldz;
@@ -408,7 +459,7 @@ __global__ __launch_bounds__(NTHREADS) void k_bwd_dz(DzArgs a) {
       const bool in = tok < rowsT;
       const float c = in ? a.g * tcoef[j] : 0.f;
       const float lb = (c != 0.f) ? tlse[j] * LOG2E : 0.f;
-      const int yrel = (in ? ttgt[j] : -1) - (int)v0 - lane_row0;
+      const int yrel = (in ? ttgt[j] - (int)a.v_off : -1) - (int)v0 - lane_row0;   // far out of range: another shard's
       const bool live = c != 0.f;                            // select: a masked token's row is exactly 0
 #pragma unroll
       for (int i = 0; i < MB; ++i)

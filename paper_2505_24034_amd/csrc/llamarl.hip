@@ -197,12 +197,15 @@ llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int6
   }
 }
 
+// W holds the vocabulary rows [v_off, v_off + V) of a head with V_total rows (the whole head: v_off = 0, V = V_total).
+// partial == 0: out0 = logp, out1 = lse.  partial != 0: (out0, out1, out2) = the shard's (m, s, zt).
 template <typename TT>
 llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets, const uint8_t* mask, int64_t N,
-                            int64_t d, int64_t V, float* logp, float* lse, char* ws, hipStream_t st) {
+                            int64_t d, int64_t V, int64_t v_off, int64_t V_total, int partial, float* out0,
+                            float* out1, float* out2, char* ws, hipStream_t st) {
   const FwdWs w = fwd_ws(N, V);
   FwdArgs a;
-  a.H = H; a.W = W; a.targets = targets; a.N = N; a.d = d; a.V = V;
+  a.H = H; a.W = W; a.targets = targets; a.N = N; a.d = d; a.V = V; a.v_off = v_off;
   a.tiles_v = w.tiles_v; a.tiles_t = w.tiles_t; a.n_pad = w.n_pad;
   a.part_m = reinterpret_cast<float*>(ws + w.off_m);
   a.part_s = reinterpret_cast<float*>(ws + w.off_s);
@@ -210,23 +213,27 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
   int32_t* rows = reinterpret_cast<int32_t*>(ws + w.off_rows);
   int32_t* n_act = reinterpret_cast<int32_t*>(ws + w.off_nact);
   a.rows = rows; a.n_act = n_act;
-  // active-token list (mask and target range); inactive rows get logp = lse = 0 here
+  // active-token list (mask and target range); inactive rows get their outputs here
   k_compact_rows<<<dim3((unsigned)((N + COMPACT_BLOCK_ROWS - 1) / COMPACT_BLOCK_ROWS)), dim3(COMPACT_THREADS), 0, st>>>(
-      0, mask, targets, V, nullptr, N, rows, n_act, logp, lse);
+      partial ? 2 : 0, mask, targets, V_total, nullptr, N, rows, n_act, out0, out1, out2);
   HIP_TRY(hipGetLastError());
   HIP_TRY(set_lds(k_fwd_partials<TT>, FWD_LDS_BYTES));
   k_fwd_partials<TT><<<dim3((unsigned)persistent_grid((int64_t)w.tiles_v * w.tiles_t)), dim3(NTHREADS), FWD_LDS_BYTES,
                        st>>>(a);
   HIP_TRY(hipGetLastError());
-  k_merge_logp<<<dim3((unsigned)((N + MERGE_TOKENS - 1) / MERGE_TOKENS)), dim3(MERGE_TOKENS * MERGE_SLICES), 0, st>>>(
-      a.part_m, a.part_s, a.zt, rows, n_act, w.tiles_v, w.n_pad, logp, lse);
+  MergeArgs m;
+  m.part_m = a.part_m; m.part_s = a.part_s; m.zt = a.zt; m.rows = rows; m.n_act = n_act; m.tiles_v = w.tiles_v;
+  m.n_pad = w.n_pad; m.out0 = out0; m.out1 = out1; m.out2 = out2; m.targets = targets; m.v_off = v_off; m.V = V;
+  const dim3 mgrid((unsigned)((N + MERGE_TOKENS - 1) / MERGE_TOKENS)), mblock(MERGE_TOKENS * MERGE_SLICES);
+  if (partial) k_merge_logp<true><<<mgrid, mblock, 0, st>>>(m);
+  else k_merge_logp<false><<<mgrid, mblock, 0, st>>>(m);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
 
 template <typename TT>
 llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, const float* lse, const float* coef,
-                       float g, int64_t N, int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
+                       float g, int64_t N, int64_t d, int64_t V, int64_t v_off, llamarl_dtype dt, void* dH, void* dW,
                        llamarl_dtype dW_dt, int accumulate_dW, char* ws, hipStream_t st, void* const* ev) {
   typedef typename TT::store_t stt;
   const BwdWs w = bwd_ws(N, d, V, dt);
@@ -243,7 +250,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
 
   // tokens that carry gradient (coef != 0), and exact zeros for the dH rows of all the others
   k_compact_rows<<<dim3((unsigned)((N + COMPACT_BLOCK_ROWS - 1) / COMPACT_BLOCK_ROWS)), dim3(COMPACT_THREADS), 0, st>>>(
-      1, nullptr, nullptr, V, coef, N, rows, n_act, nullptr, nullptr);
+      1, nullptr, nullptr, V, coef, N, rows, n_act, nullptr, nullptr, nullptr);
   HIP_TRY(hipGetLastError());
   k_zero_inactive_rows<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(reinterpret_cast<stt*>(dH), coef, N, d);
   HIP_TRY(hipGetLastError());
@@ -263,6 +270,7 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   // recompute logits tile by tile, turn them into dz (rows / columns = list positions)
   DzArgs a;
   a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
+  a.v_off = v_off;
   a.tiles_v = (int)((V + BM - 1) / BM);
   a.tiles_t = (int)((N + BN - 1) / BN);
   a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.rows = rows; a.n_act = n_act;
@@ -327,12 +335,16 @@ size_t llamarl_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt
   }
 }
 
-llamarl_status llamarl_token_logprobs(const void* H, const void* W, const int32_t* targets, const uint8_t* mask,
-                                      int64_t N, int64_t d, int64_t V, llamarl_dtype dt, float* logp, float* lse,
-                                      void* ws, size_t ws_bytes, void* stream) {
-  if (!H || !W || !targets || !logp || !lse) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+static llamarl_status logprobs_entry(const void* H, const void* W, const int32_t* targets, const uint8_t* mask, int64_t N,
+                                     int64_t d, int64_t V, int64_t v_off, int64_t V_total, llamarl_dtype dt, int partial,
+                                     float* out0, float* out1, float* out2, void* ws, size_t ws_bytes, void* stream) {
+  if (!H || !W || !targets || !out0 || !out1 || (partial && !out2))
+    return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
   llamarl_status s = check_head_shape(N, d, V, dt);
   if (s != LLAMARL_OK) return s;
+  if (v_off < 0 || V_total >= ((int64_t)1 << 31) || v_off + V > V_total)
+    return fail(LLAMARL_ERR_INVALID_ARG, "vocabulary slice [%lld, %lld) does not lie inside [0, %lld)", (long long)v_off,
+                (long long)(v_off + V), (long long)V_total);
   if (!aligned16(H) || !aligned16(W)) return fail(LLAMARL_ERR_INVALID_ARG, "H and W must be 16-byte aligned");
   const size_t need = fwd_ws(N, V).total;
   if (!ws || ws_bytes < need)
@@ -340,8 +352,34 @@ llamarl_status llamarl_token_logprobs(const void* H, const void* W, const int32_
   if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (dt == LLAMARL_BF16)
-    return run_logprobs<BF16>(H, W, targets, mask, N, d, V, logp, lse, reinterpret_cast<char*>(ws), st);
-  return run_logprobs<F32>(H, W, targets, mask, N, d, V, logp, lse, reinterpret_cast<char*>(ws), st);
+    return run_logprobs<BF16>(H, W, targets, mask, N, d, V, v_off, V_total, partial, out0, out1, out2,
+                              reinterpret_cast<char*>(ws), st);
+  return run_logprobs<F32>(H, W, targets, mask, N, d, V, v_off, V_total, partial, out0, out1, out2,
+                           reinterpret_cast<char*>(ws), st);
+}
+
+llamarl_status llamarl_token_logprobs(const void* H, const void* W, const int32_t* targets, const uint8_t* mask,
+                                      int64_t N, int64_t d, int64_t V, llamarl_dtype dt, float* logp, float* lse,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  return logprobs_entry(H, W, targets, mask, N, d, V, 0, V, dt, 0, logp, lse, nullptr, ws, ws_bytes, stream);
+}
+
+llamarl_status llamarl_token_logprobs_partial(const void* H, const void* W_slice, const int32_t* targets,
+                                              const uint8_t* mask, int64_t N, int64_t d, int64_t V_slice, int64_t v0,
+                                              int64_t V_total, llamarl_dtype dt, float* m, float* s, float* zt,
+                                              void* ws, size_t ws_bytes, void* stream) {
+  return logprobs_entry(H, W_slice, targets, mask, N, d, V_slice, v0, V_total, dt, 1, m, s, zt, ws, ws_bytes, stream);
+}
+
+llamarl_status llamarl_merge_partials(const float* m, const float* s, const float* zt, int shards, int64_t N,
+                                      float* logp, float* lse, void* stream) {
+  if (!m || !s || !zt || !logp || !lse) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  if (shards <= 0 || N <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "shards and N must be positive");
+  if (N >= ((int64_t)1 << 39)) return fail(LLAMARL_ERR_UNSUPPORTED, "too many tokens");
+  k_merge_shards<<<dim3((unsigned)((N + 255) / 256)), dim3(256), 0, reinterpret_cast<hipStream_t>(stream)>>>(
+      m, s, zt, shards, N, logp, lse);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
 }
 
 static llamarl_status check_loss_args(const float* logp, const float* mu_logp, const float* adv, const uint8_t* mask,
@@ -440,7 +478,7 @@ llamarl_status llamarl_offpolicy_loss_fwd_static(const float* logp, const float*
 }
 
 static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* targets, const float* lse,
-                                const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
+                                const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V, int64_t v_off,
                                 llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt, int accumulate_dW,
                                 void* ws, size_t ws_bytes, void* stream, void* const* ev) {
   if (!H || !W || !targets || !lse || !coef || !dH || !dW) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
@@ -451,15 +489,16 @@ static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* tar
   if (!aligned16(H) || !aligned16(W) || !aligned16(dH) || !aligned16(dW))
     return fail(LLAMARL_ERR_INVALID_ARG, "H, W, dH, dW must be 16-byte aligned");
   if (!std::isfinite(grad_loss)) return fail(LLAMARL_ERR_INVALID_ARG, "grad_loss must be finite");
+  if (v_off < 0 || v_off + V >= ((int64_t)1 << 31)) return fail(LLAMARL_ERR_INVALID_ARG, "bad vocabulary offset");
   const size_t need = bwd_ws(N, d, V, dt).total;
   if (!ws || ws_bytes < need)
     return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, need);
   if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (dt == LLAMARL_BF16)
-    return run_bwd<BF16>(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW,
+    return run_bwd<BF16>(H, W, targets, lse, coef, grad_loss, N, d, V, v_off, dt, dH, dW, dW_dt, accumulate_dW,
                          reinterpret_cast<char*>(ws), st, ev);
-  return run_bwd<F32>(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW,
+  return run_bwd<F32>(H, W, targets, lse, coef, grad_loss, N, d, V, v_off, dt, dH, dW, dW_dt, accumulate_dW,
                       reinterpret_cast<char*>(ws), st, ev);
 }
 
@@ -467,8 +506,17 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
                                           llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
-  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes, stream,
-                   nullptr);
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes,
+                   stream, nullptr);
+}
+
+llamarl_status llamarl_offpolicy_loss_bwd_slice(const void* H, const void* W_slice, const int32_t* targets,
+                                                const float* lse, const float* coef, float grad_loss, int64_t N,
+                                                int64_t d, int64_t V_slice, int64_t v0, llamarl_dtype dt,
+                                                void* dH_partial, void* dW_slice, llamarl_dtype dW_dt,
+                                                int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
+  return bwd_entry(H, W_slice, targets, lse, coef, grad_loss, N, d, V_slice, v0, dt, dH_partial, dW_slice, dW_dt,
+                   accumulate_dW, ws, ws_bytes, stream, nullptr);
 }
 
 llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, const int32_t* targets,
@@ -479,8 +527,8 @@ llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, c
   if (!phase_events) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events is null");
   for (int i = 0; i < 6; ++i)
     if (!phase_events[i]) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events[%d] is null", i);
-  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes, stream,
-                   phase_events);
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes,
+                   stream, phase_events);
 }
 
 llamarl_status llamarl_mfma_ceiling(int iters, float* sink, double* flops, void* stream) {

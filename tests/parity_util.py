@@ -70,3 +70,36 @@ def check_all(got, ref, dtype, check_stats=True):
         assert np.allclose(st[1:4], ref["stats"][1:4], rtol=0, atol=(1e-4 if dtype == "f32" else 2.5e-2))
     check_grad("dH", f64(got["dH"]), ref["dH"], dtype)
     check_grad("dW", f64(got["dW"]), ref["dW"], dtype)
+
+
+def sample_rows(x, n, rng):
+    """Valid rows: first / last valid token of every generation, rows next to 256-row tile edges, random ones."""
+    mask = x["mask"].cpu().numpy()
+    B, T = mask.shape
+    valid = np.nonzero(mask.reshape(-1))[0]
+    picks = []
+    for b in range(B):
+        ln = int(mask[b].sum())
+        if ln:
+            picks += [b * T, b * T + ln - 1]
+    vs = set(valid.tolist())
+    for e in (255, 256, 257, 511, 512):
+        picks += [r for r in (e, valid[-1] - e) if r in vs]
+    extra = rng.choice(valid, size=max(0, n - len(set(picks))), replace=False)
+    return np.array(sorted(set(picks) | set(extra.tolist())))[: max(n, len(set(picks)))]
+
+
+def oracle_forward_over_valid_rows(x, Wd, chunk=1024):
+    """fp64 oracle log-probs / lse of EVERY valid row, in row chunks (rows are independent).  Inputs only: nothing
+    the HIP library produced is read here."""
+    mask_flat = synth.to_oracle(x["mask"]).reshape(-1)
+    N = mask_flat.size
+    valid = np.nonzero(mask_flat)[0]
+    o_logp, o_lse = np.zeros(N), np.zeros(N)
+    for c0 in range(0, valid.size, chunk):
+        r = valid[c0:c0 + chunk]
+        ridx = torch.as_tensor(r, device="cuda")
+        lp, ls = orc.token_logprobs(synth.to_oracle(x["H"][ridx]), Wd, synth.to_oracle(x["targets"][ridx]))
+        o_logp[r], o_lse[r] = lp, ls
+        print("oracle forward rows", c0 + r.size, "/", valid.size, flush=True)
+    return valid, o_logp, o_lse

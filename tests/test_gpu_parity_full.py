@@ -15,42 +15,9 @@ import torch
 
 from oracle import aipo_oracle as orc
 import synth
-from parity_util import check_grad, f64
+from parity_util import check_grad, f64, oracle_forward_over_valid_rows, sample_rows
 
 pytestmark = pytest.mark.gpu
-
-
-def _sample_rows(x, n, rng):
-    """Valid rows: first / last valid token of every generation, rows next to 256-row tile edges, random ones."""
-    mask = x["mask"].cpu().numpy()
-    B, T = mask.shape
-    valid = np.nonzero(mask.reshape(-1))[0]
-    picks = []
-    for b in range(B):
-        ln = int(mask[b].sum())
-        if ln:
-            picks += [b * T, b * T + ln - 1]
-    vs = set(valid.tolist())
-    for e in (255, 256, 257, 511, 512):
-        picks += [r for r in (e, valid[-1] - e) if r in vs]
-    extra = rng.choice(valid, size=max(0, n - len(set(picks))), replace=False)
-    return np.array(sorted(set(picks) | set(extra.tolist())))[: max(n, len(set(picks)))]
-
-
-def _oracle_forward_over_valid_rows(x, Wd, chunk=1024):
-    """fp64 oracle log-probs / lse of EVERY valid row, in row chunks (rows are independent).  Inputs only: nothing
-    the HIP library produced is read here."""
-    mask_flat = synth.to_oracle(x["mask"]).reshape(-1)
-    N = mask_flat.size
-    valid = np.nonzero(mask_flat)[0]
-    o_logp, o_lse = np.zeros(N), np.zeros(N)
-    for c0 in range(0, valid.size, chunk):
-        r = valid[c0:c0 + chunk]
-        ridx = torch.as_tensor(r, device="cuda")
-        lp, ls = orc.token_logprobs(synth.to_oracle(x["H"][ridx]), Wd, synth.to_oracle(x["targets"][ridx]))
-        o_logp[r], o_lse[r] = lp, ls
-        print("oracle forward rows", c0 + r.size, "/", valid.size, flush=True)
-    return valid, o_logp, o_lse
 
 
 def _check_loss_outputs(got_loss, got_coef, got_stats, o, o_logp):
@@ -95,7 +62,7 @@ def test_full_size_workload(lib, name, n_rows, n_dw_rows):
     # ---- every log-prob, lse, coef, the loss and the statistics against one fp64 forward over all valid rows.
     # Every argument of every orc.* call below is an input of the workload or an oracle result.
     Ws = orc.widen(synth.to_oracle(x["W"]))
-    valid, o_logp, o_lse = _oracle_forward_over_valid_rows(x, Ws)
+    valid, o_logp, o_lse = oracle_forward_over_valid_rows(x, Ws)
     assert valid.size == n_valid
     assert np.abs(f64(logp) - o_logp).max() <= 2e-2
     assert np.abs(f64(lse) - o_lse).max() <= 2e-2
@@ -119,7 +86,7 @@ def test_full_size_workload(lib, name, n_rows, n_dw_rows):
 
     # ---- dH of a sample of rows: oracle backward from the oracle's own lse and coef
     rng = np.random.default_rng(w.seed)
-    rows = _sample_rows(x, n_rows, rng)
+    rows = sample_rows(x, n_rows, rng)
     ridx = torch.as_tensor(rows, device="cuda")
     o_dH, _ = orc.offpolicy_loss_bwd(synth.to_oracle(x["H"][ridx]), Ws, o_tg[rows], o_lse[rows], o["coef"][rows])
     check_grad("dH[sampled rows]", f64(dH[ridx]), o_dH, "bf16")
@@ -127,7 +94,7 @@ def test_full_size_workload(lib, name, n_rows, n_dw_rows):
     # ---- the whole dW of a pass whose gradient weight lives on a sample of rows (dW is linear in coef): the
     # library gets its own coef restricted to those rows, the oracle its own
     if n_dw_rows:
-        drows = _sample_rows(x, n_dw_rows, rng)
+        drows = sample_rows(x, n_dw_rows, rng)
         didx = torch.as_tensor(drows, device="cuda")
         coef_s = torch.zeros_like(coef)
         coef_s[didx] = coef[didx]
@@ -160,7 +127,7 @@ def test_config2_every_output_against_the_oracle(lib):
     torch.cuda.synchronize()
 
     Wd = orc.widen(synth.to_oracle(x["W"]))
-    valid, o_logp, o_lse = _oracle_forward_over_valid_rows(x, Wd)
+    valid, o_logp, o_lse = oracle_forward_over_valid_rows(x, Wd)
     chunk = 1024
     assert np.abs(f64(logp) - o_logp).max() <= 2e-2 and np.abs(f64(lse) - o_lse).max() <= 2e-2
     o = orc.offpolicy_loss_fwd(o_logp, synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]),
