@@ -178,6 +178,24 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * llamarl_offpolicy_loss_bwd with a bounded workspace.  The backward stages dz for the rows it works on; by default
+ * that is every row of the batch (workspace ~ 2 * V * N bytes for bf16).  With max_rows_per_pass = R > 0 (rounded up
+ * to a multiple of 256) it takes the active rows (coef != 0) R at a time: the workspace holds dz for R rows only,
+ * each pass writes the dH rows of its tokens and adds its share to dW (the first pass stores, or adds if
+ * accumulate_dW).  ceil(N / R) passes are enqueued whatever the number of active rows; passes past them find
+ * nothing to do and cost microseconds.  A caller who knows that at most R rows are active bounds the workspace at
+ * no cost; a smaller R trades it for one read-modify-write of dW per extra pass -- and, for a bf16 dW, one more
+ * rounding to bf16 per pass (use dW_dt = LLAMARL_F32 when that matters).  max_rows_per_pass = 0 means N.
+ *   ws >= llamarl_bwd_workspace_bytes(N, d, V, dt, max_rows_per_pass)   (returns 0 for invalid sizes)
+ */
+size_t llamarl_bwd_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows_per_pass);
+llamarl_status llamarl_offpolicy_loss_bwd_chunked(const void* H, const void* W, const int32_t* targets,
+                                                  const float* lse, const float* coef, float grad_loss, int64_t N,
+                                                  int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
+                                                  llamarl_dtype dW_dt, int accumulate_dW, int64_t max_rows_per_pass,
+                                                  void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Vocabulary-sharded head (Sec. 8.2, Table 3: the trainer runs with model parallelism 8-32, i.e. every device
  * holds a slice of the head's vocabulary rows).  These three calls are one shard's share of the path; the exchange
  * between shards (an all-reduce of 12 bytes per token, a reduce-scatter of dH) is the caller's.  On one GPU the

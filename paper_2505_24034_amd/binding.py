@@ -23,7 +23,7 @@ EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "
            "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
            "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling",
            "llamarl_offpolicy_loss_fwd_static", "llamarl_token_logprobs_partial", "llamarl_merge_partials",
-           "llamarl_offpolicy_loss_bwd_slice")
+           "llamarl_offpolicy_loss_bwd_slice", "llamarl_bwd_workspace_bytes", "llamarl_offpolicy_loss_bwd_chunked")
 
 
 class LlamarlError(RuntimeError):
@@ -79,6 +79,11 @@ def load():
     lib.llamarl_offpolicy_loss_bwd_slice.restype = ci
     lib.llamarl_offpolicy_loss_bwd_slice.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, i64, ci, vp, vp, ci, ci, vp,
                                                      sz, vp]
+    lib.llamarl_bwd_workspace_bytes.restype = sz
+    lib.llamarl_bwd_workspace_bytes.argtypes = [i64, i64, i64, ci, i64]
+    lib.llamarl_offpolicy_loss_bwd_chunked.restype = ci
+    lib.llamarl_offpolicy_loss_bwd_chunked.argtypes = [vp, vp, vp, vp, vp, cf, i64, i64, i64, ci, vp, vp, ci, ci, i64,
+                                                       vp, sz, vp]
     lib.llamarl_mfma_ceiling.restype = ci
     lib.llamarl_mfma_ceiling.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -197,10 +202,15 @@ def offpolicy_loss_fwd_static(logp, mu_logp, adv, mask, B, T, loss, coef, stats,
     return loss, coef, stats
 
 
+def bwd_workspace_bytes(N, d, V, dt, max_rows_per_pass):
+    return int(load().llamarl_bwd_workspace_bytes(N, d, V, dt, max_rows_per_pass))
+
+
 def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0, dW_dtype=None, dW=None, accumulate_dW=False,
-                       dH=None, ws=None, stream=None, phase_events=None):
+                       dH=None, ws=None, stream=None, phase_events=None, max_rows_per_pass=None):
     """llamarl_offpolicy_loss_bwd: returns (dH [N,d] in H's dtype, dW [V,d] in dW_dtype).
-    phase_events: six raw hipEvent_t handles (ints) -> llamarl_offpolicy_loss_bwd_phases is called instead."""
+    phase_events: six raw hipEvent_t handles (ints) -> llamarl_offpolicy_loss_bwd_phases is called instead.
+    max_rows_per_pass: -> llamarl_offpolicy_loss_bwd_chunked (workspace for that many active rows at a time)."""
     lib = load()
     dt = _dtype_code(H)
     _need(H, H.dtype, "H"); _need(W, H.dtype, "W"); _need(targets, torch.int32, "targets")
@@ -218,6 +228,12 @@ def offpolicy_loss_bwd(H, W, targets, lse, coef, grad_loss=1.0, dW_dtype=None, d
     if dH is None:
         dH = torch.empty(N, d, dtype=H.dtype, device=H.device)
     _need(dW, dW_dtype, "dW"); _need(dH, H.dtype, "dH")
+    if max_rows_per_pass is not None:
+        ws = _workspace(bwd_workspace_bytes(N, d, V, dt, int(max_rows_per_pass)), H.device, ws)
+        _check(lib.llamarl_offpolicy_loss_bwd_chunked(
+            _ptr(H), _ptr(W), _ptr(targets), _ptr(lse), _ptr(coef), float(grad_loss), N, d, V, dt, _ptr(dH), _ptr(dW),
+            _dtype_code(dW), int(bool(accumulate_dW)), int(max_rows_per_pass), _ptr(ws), ws.numel(), _stream(stream)))
+        return dH, dW
     ws = _workspace(workspace_bytes(N, d, V, dt, PASS_LOSS_BWD), H.device, ws)
     args = (_ptr(H), _ptr(W), _ptr(targets), _ptr(lse), _ptr(coef), float(grad_loss), N, d, V, dt, _ptr(dH), _ptr(dW),
             _dtype_code(dW), int(bool(accumulate_dW)), _ptr(ws), ws.numel(), _stream(stream))

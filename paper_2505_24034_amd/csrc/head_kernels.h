@@ -596,6 +596,8 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   typedef typename TT::store_t st;
   const int64_t M = a.m_count ? (int64_t)*a.m_count : a.M;
   const int64_t K = a.k_count ? ((int64_t)*a.k_count + 63) / 64 * 64 : a.K;
+  // a later pass of a chunked backward that found no active rows: nothing to add to what the output holds
+  if ((MODE == 2 || MODE == 4) && a.k_count != nullptr && K == 0) return;
   if (a.pitch_count != nullptr) {                    // kernel arguments are a private copy
     const int64_t pp = packed_pitch(*a.pitch_count);
     if (a.packed_a) a.lda = pp;

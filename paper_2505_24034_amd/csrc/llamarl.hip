@@ -85,34 +85,39 @@ std::mutex g_scratch_mutex;
 void* g_scratch_ptr[STATIC_MAX_DEVICES] = {};      // device address of `scratch` on each GPU, looked up once
 
 struct BwdWs {
-  int64_t ldz, ldzt;  // padded leading dimensions (elements): V and N rounded up to 64
+  int64_t R;          // active rows one pass takes (a multiple of 256, or N): dz, the operand panels and the split
+                      // partials are sized for R rows; more active rows than that are taken in further passes
+  int n_pass;         // passes the host enqueues = ceil(N / R); passes past the active rows find nothing to do
+  int64_t ldz, ldzt;  // padded leading dimensions (elements): V rounded up to 64; packed_pitch(R)
   size_t off_dz, off_dzt, off_wt, off_ht, off_rows, off_nact, off_part, total;
   int dh_splits;      // K splits of the dH contraction (1 = none)
 };
-BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt) {
+BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows_per_pass) {
   BwdWs w;
   const size_t es = esize(dt);
+  w.R = (max_rows_per_pass <= 0 || max_rows_per_pass >= N) ? N : std::min(N, round_up(max_rows_per_pass, BN));
+  w.n_pass = (int)((N + w.R - 1) / w.R);
   w.ldz = round_up(V, 64);
-  w.ldzt = packed_pitch(N);          // the kernels use packed_pitch(active rows) <= this
+  w.ldzt = packed_pitch(w.R);        // the kernels use packed_pitch(active rows of the pass) <= this
   // bf16: dz exists in the vocab-major orientation only and W is read as it is (k-major dH contraction);
   // fp32 keeps a token-major dz and a transposed copy of W as well
   const bool both = dt == LLAMARL_F32;
   w.off_dz = 0;
-  w.off_dzt = w.off_dz + (both ? (size_t)round_up(N * w.ldz * (int64_t)es, 256) : 0);
+  w.off_dzt = w.off_dz + (both ? (size_t)round_up(w.R * w.ldz * (int64_t)es, 256) : 0);
   w.off_wt = w.off_dzt + (size_t)round_up(V * w.ldzt * (int64_t)es, 256);
   w.off_ht = w.off_wt + (both ? (size_t)round_up(d * w.ldz * (int64_t)es, 256) : 0);
   w.off_rows = w.off_ht + (size_t)round_up(d * w.ldzt * (int64_t)es, 256);
-  w.off_nact = w.off_rows + (size_t)round_up(w.ldzt * (int64_t)sizeof(int32_t), 256);
-  w.off_part = w.off_nact + 256;
-  // dH has few output tiles (N/256 x d/256) with a very long K = V: split K until there are enough work items
+  w.off_nact = w.off_rows + (size_t)round_up(round_up(N, 64) * (int64_t)sizeof(int32_t), 256);
+  w.off_part = w.off_nact + (size_t)round_up((int64_t)(1 + w.n_pass) * (int64_t)sizeof(int32_t), 256);
+  // dH has few output tiles (rows/256 x d/256) with a very long K = V: split K until there are enough work items
   // to fill 256 CUs evenly (at most ~1/16 of the last round idle) whatever the number of active rows turns out to
   // be, as long as a split keeps at least four K slabs (64 bf16 / 32 fp32 elements each).  d % 4 keeps float4 rows.
-  const int64_t tiles = ((N + BM - 1) / BM) * ((d + BN - 1) / BN);
+  const int64_t tiles = ((w.R + BM - 1) / BM) * ((d + BN - 1) / BN);
   const int64_t slabs = dt == LLAMARL_BF16 ? (V + 63) / 64 : w.ldz / 32;
   int s = 1;
   while (s < 8 && tiles * s < 8192 && slabs / (s * 2) >= 4) s *= 2;
   w.dh_splits = s;
-  w.total = w.off_part + (s > 1 ? (size_t)round_up((int64_t)s * N * d * 4, 256) : 0);
+  w.total = w.off_part + (s > 1 ? (size_t)round_up((int64_t)s * w.R * d * 4, 256) : 0);
   return w;
 }
 
@@ -231,13 +236,22 @@ llamarl_status run_logprobs(const void* H, const void* W, const int32_t* targets
   return LLAMARL_OK;
 }
 
+// active rows of each pass: cnt[c] = clamp(n_act - c * R, 0, R)
+__global__ void k_pass_counts(const int32_t* n_act, int64_t R, int n_pass, int32_t* cnt) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n_pass) return;
+  const int64_t left = (int64_t)*n_act - (int64_t)c * R;
+  cnt[c] = (int32_t)(left < 0 ? 0 : (left > R ? R : left));
+}
+
 template <typename TT>
 llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, const float* lse, const float* coef,
                        float g, int64_t N, int64_t d, int64_t V, int64_t v_off, llamarl_dtype dt, void* dH, void* dW,
-                       llamarl_dtype dW_dt, int accumulate_dW, char* ws, hipStream_t st, void* const* ev) {
+                       llamarl_dtype dW_dt, int accumulate_dW, int64_t max_rows_per_pass, char* ws, hipStream_t st,
+                       void* const* ev) {
   typedef typename TT::store_t stt;
-  const BwdWs w = bwd_ws(N, d, V, dt);
-  // ev (optional, 6 caller-owned hipEvent_t): recorded on the stream at the phase boundaries
+  const BwdWs w = bwd_ws(N, d, V, dt, max_rows_per_pass);
+  // ev (optional, 6 caller-owned hipEvent_t): recorded on the stream at the phase boundaries of a one-pass backward
 #define PHASE_EVENT(i) \
   do { if (ev) HIP_TRY(hipEventRecord(reinterpret_cast<hipEvent_t>(ev[i]), st)); } while (0)
   PHASE_EVENT(0);
@@ -245,69 +259,81 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   stt* dzt = reinterpret_cast<stt*>(ws + w.off_dzt);
   stt* wt = reinterpret_cast<stt*>(ws + w.off_wt);
   stt* ht = reinterpret_cast<stt*>(ws + w.off_ht);
-  int32_t* rows = reinterpret_cast<int32_t*>(ws + w.off_rows);
-  int32_t* n_act = reinterpret_cast<int32_t*>(ws + w.off_nact);
+  int32_t* all_rows = reinterpret_cast<int32_t*>(ws + w.off_rows);
+  int32_t* n_act_all = reinterpret_cast<int32_t*>(ws + w.off_nact);
+  int32_t* pass_cnt = n_act_all + 1;
 
   // tokens that carry gradient (coef != 0), and exact zeros for the dH rows of all the others
   k_compact_rows<<<dim3((unsigned)((N + COMPACT_BLOCK_ROWS - 1) / COMPACT_BLOCK_ROWS)), dim3(COMPACT_THREADS), 0, st>>>(
-      1, nullptr, nullptr, V, coef, N, rows, n_act, nullptr, nullptr, nullptr);
+      1, nullptr, nullptr, V, coef, N, all_rows, n_act_all, nullptr, nullptr, nullptr);
   HIP_TRY(hipGetLastError());
   k_zero_inactive_rows<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(reinterpret_cast<stt*>(dH), coef, N, d);
   HIP_TRY(hipGetLastError());
-
+  if (w.n_pass > 1) {
+    k_pass_counts<<<dim3((unsigned)((w.n_pass + 255) / 256)), dim3(256), 0, st>>>(n_act_all, w.R, w.n_pass, pass_cnt);
+    HIP_TRY(hipGetLastError());
+  }
   constexpr bool kBf16 = sizeof(stt) == 2;
-  // operand panels: H^T [d][ldzt] of the active tokens (dW contraction); fp32 also needs W^T [d][ldz]
-  if (!kBf16) {
+  if (!kBf16) {   // fp32 only: W^T [d][ldz] for the K-contiguous dH contraction
     k_transpose<stt><<<dim3((unsigned)(w.ldz / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
         reinterpret_cast<const stt*>(W), V, d, d, wt, w.ldz, nullptr, nullptr);
     HIP_TRY(hipGetLastError());
   }
-  k_transpose<stt><<<dim3((unsigned)(w.ldzt / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
-      reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, rows, n_act);
-  HIP_TRY(hipGetLastError());
 
-  PHASE_EVENT(1);
-  // recompute logits tile by tile, turn them into dz (rows / columns = list positions)
-  DzArgs a;
-  a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
-  a.v_off = v_off;
-  a.tiles_v = (int)((V + BM - 1) / BM);
-  a.tiles_t = (int)((N + BN - 1) / BN);
-  a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.rows = rows; a.n_act = n_act;
-  const int dz_lds = MAINLOOP_LDS_BYTES;
-  HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
-  k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
-  HIP_TRY(hipGetLastError());
-
-  PHASE_EVENT(2);
-  // dH [active rows, d] = dz [n_act,V] . W [V,d], scattered to the token rows.
-  //   bf16: k-major operands dz^T [V][n_act] and W [V][d], K = V exactly
-  //   fp32: K-contiguous operands dz [n_act][ldz] and W^T [d][ldz], K zero-padded to ldz
-  llamarl_status s;
-  float* part = reinterpret_cast<float*>(ws + w.off_part);
-  void* dh_out = w.dh_splits > 1 ? static_cast<void*>(part) : dH;
-  const int dh_f32 = w.dh_splits > 1 ? 1 : (dt == LLAMARL_F32);
-  const int32_t* dh_scatter = w.dh_splits > 1 ? nullptr : rows;
-  if constexpr (kBf16) {
-    s = launch_store_gemm<TT, true>(dzt, w.ldzt, W, d, N, d, V, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
-                                    w.dh_splits, N * d, n_act, 1, 0, st);
-  } else {
-    s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, N, d, w.ldz, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
-                              w.dh_splits, N * d, nullptr, 0, 0, st);
-  }
-  if (s != LLAMARL_OK) return s;
-  PHASE_EVENT(3);
-  if (w.dh_splits > 1) {
-    k_reduce_splits<stt><<<dim3((unsigned)N), dim3(256), 0, st>>>(part, w.dh_splits, N * d, rows, n_act, d,
-                                                                 reinterpret_cast<stt*>(dH), d);
+  for (int c = 0; c < w.n_pass; ++c) {
+    // this pass: list positions [c R, c R + n_act), n_act = the pass's own count (device scalar)
+    const int32_t* rows = all_rows + (int64_t)c * w.R;
+    const int32_t* n_act = w.n_pass > 1 ? pass_cnt + c : n_act_all;
+    const int64_t Rc = std::min(w.R, N - (int64_t)c * w.R);       // rows the pass can hold at most
+    // operand panel H^T [d][pitch] of the pass's tokens (dW contraction)
+    k_transpose<stt><<<dim3((unsigned)(w.ldzt / 64), (unsigned)((d + 63) / 64)), dim3(256), 0, st>>>(
+        reinterpret_cast<const stt*>(H), N, d, d, ht, w.ldzt, rows, n_act);
     HIP_TRY(hipGetLastError());
+    if (c == 0) PHASE_EVENT(1);
+
+    // recompute logits tile by tile, turn them into dz (rows / columns = list positions of the pass)
+    DzArgs a;
+    a.H = H; a.W = W; a.targets = targets; a.lse = lse; a.coef = coef; a.g = g; a.N = N; a.d = d; a.V = V;
+    a.v_off = v_off;
+    a.tiles_v = (int)((V + BM - 1) / BM);
+    a.tiles_t = (int)((Rc + BN - 1) / BN);
+    a.dz = dz; a.ldz = w.ldz; a.dzt = dzt; a.rows = rows; a.n_act = n_act;
+    const int dz_lds = MAINLOOP_LDS_BYTES;
+    HIP_TRY(set_lds(k_bwd_dz<TT>, dz_lds));
+    k_bwd_dz<TT><<<dim3((unsigned)persistent_grid((int64_t)a.tiles_v * a.tiles_t)), dim3(NTHREADS), dz_lds, st>>>(a);
+    HIP_TRY(hipGetLastError());
+    if (c == 0) PHASE_EVENT(2);
+
+    // dH [active rows, d] = dz [n_act,V] . W [V,d], scattered to the token rows.
+    //   bf16: k-major operands dz^T [V][n_act] and W [V][d], K = V exactly
+    //   fp32: K-contiguous operands dz [n_act][ldz] and W^T [d][ldz], K zero-padded to ldz
+    llamarl_status s;
+    float* part = reinterpret_cast<float*>(ws + w.off_part);
+    void* dh_out = w.dh_splits > 1 ? static_cast<void*>(part) : dH;
+    const int dh_f32 = w.dh_splits > 1 ? 1 : (dt == LLAMARL_F32);
+    const int32_t* dh_scatter = w.dh_splits > 1 ? nullptr : rows;
+    if constexpr (kBf16) {
+      s = launch_store_gemm<TT, true>(dzt, w.ldzt, W, d, Rc, d, V, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
+                                      w.dh_splits, w.R * d, n_act, 1, 0, st);
+    } else {
+      s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, Rc, d, w.ldz, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
+                                w.dh_splits, w.R * d, nullptr, 0, 0, st);
+    }
+    if (s != LLAMARL_OK) return s;
+    if (c == 0) PHASE_EVENT(3);
+    if (w.dh_splits > 1) {
+      k_reduce_splits<stt><<<dim3((unsigned)Rc), dim3(256), 0, st>>>(part, w.dh_splits, w.R * d, rows, n_act, d,
+                                                                    reinterpret_cast<stt*>(dH), d);
+      HIP_TRY(hipGetLastError());
+    }
+    if (c == 0) PHASE_EVENT(4);
+    // dW [V,d] (+)= dz^T [V,n_act] . H^T[d,n_act]^T      (K = n_act, zero-padded to a multiple of 64); passes after
+    // the first add to what the earlier ones stored
+    s = launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32,
+                              c == 0 ? accumulate_dW : 1, nullptr, n_act, nullptr, 1, 0, n_act, 1, 1, st);
+    if (s != LLAMARL_OK) return s;
+    if (c == 0) PHASE_EVENT(5);
   }
-  PHASE_EVENT(4);
-  // dW [V,d] = dz^T [V,n_act] . H^T[d,n_act]^T          (K = n_act, zero-padded to a multiple of 64)
-  s = launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32, accumulate_dW, nullptr,
-                            n_act, nullptr, 1, 0, n_act, 1, 1, st);
-  if (s != LLAMARL_OK) return s;
-  PHASE_EVENT(5);
 #undef PHASE_EVENT
   return LLAMARL_OK;
 }
@@ -329,7 +355,7 @@ size_t llamarl_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt
       return loss_ws(N, N).total;     // sized for the worst case B = N
     case LLAMARL_PASS_LOSS_BWD:
       if (V <= 0 || d <= 0 || (dt != LLAMARL_F32 && dt != LLAMARL_BF16)) return 0;
-      return bwd_ws(N, d, V, dt).total;
+      return bwd_ws(N, d, V, dt, 0).total;
     default:
       return 0;
   }
@@ -480,7 +506,7 @@ llamarl_status llamarl_offpolicy_loss_fwd_static(const float* logp, const float*
 static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* targets, const float* lse,
                                 const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V, int64_t v_off,
                                 llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt, int accumulate_dW,
-                                void* ws, size_t ws_bytes, void* stream, void* const* ev) {
+                                int64_t max_rows_per_pass, void* ws, size_t ws_bytes, void* stream, void* const* ev) {
   if (!H || !W || !targets || !lse || !coef || !dH || !dW) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
   llamarl_status s = check_head_shape(N, d, V, dt);
   if (s != LLAMARL_OK) return s;
@@ -490,15 +516,18 @@ static llamarl_status bwd_entry(const void* H, const void* W, const int32_t* tar
     return fail(LLAMARL_ERR_INVALID_ARG, "H, W, dH, dW must be 16-byte aligned");
   if (!std::isfinite(grad_loss)) return fail(LLAMARL_ERR_INVALID_ARG, "grad_loss must be finite");
   if (v_off < 0 || v_off + V >= ((int64_t)1 << 31)) return fail(LLAMARL_ERR_INVALID_ARG, "bad vocabulary offset");
-  const size_t need = bwd_ws(N, d, V, dt).total;
+  if (max_rows_per_pass < 0) return fail(LLAMARL_ERR_INVALID_ARG, "max_rows_per_pass must not be negative");
+  const size_t need = bwd_ws(N, d, V, dt, max_rows_per_pass).total;
   if (!ws || ws_bytes < need)
     return fail(LLAMARL_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", ws ? ws_bytes : (size_t)0, need);
   if (!aligned16(ws)) return fail(LLAMARL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (dt == LLAMARL_BF16)
     return run_bwd<BF16>(H, W, targets, lse, coef, grad_loss, N, d, V, v_off, dt, dH, dW, dW_dt, accumulate_dW,
+                         max_rows_per_pass,
                          reinterpret_cast<char*>(ws), st, ev);
   return run_bwd<F32>(H, W, targets, lse, coef, grad_loss, N, d, V, v_off, dt, dH, dW, dW_dt, accumulate_dW,
+                      max_rows_per_pass,
                       reinterpret_cast<char*>(ws), st, ev);
 }
 
@@ -506,8 +535,22 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
                                           const float* coef, float grad_loss, int64_t N, int64_t d, int64_t V,
                                           llamarl_dtype dt, void* dH, void* dW, llamarl_dtype dW_dt,
                                           int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
-  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes,
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, 0, ws, ws_bytes,
                    stream, nullptr);
+}
+
+size_t llamarl_bwd_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows_per_pass) {
+  if (N <= 0 || V <= 0 || d <= 0 || max_rows_per_pass < 0 || (dt != LLAMARL_F32 && dt != LLAMARL_BF16)) return 0;
+  return bwd_ws(N, d, V, dt, max_rows_per_pass).total;
+}
+
+llamarl_status llamarl_offpolicy_loss_bwd_chunked(const void* H, const void* W, const int32_t* targets,
+                                                  const float* lse, const float* coef, float grad_loss, int64_t N,
+                                                  int64_t d, int64_t V, llamarl_dtype dt, void* dH, void* dW,
+                                                  llamarl_dtype dW_dt, int accumulate_dW, int64_t max_rows_per_pass,
+                                                  void* ws, size_t ws_bytes, void* stream) {
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, max_rows_per_pass,
+                   ws, ws_bytes, stream, nullptr);
 }
 
 llamarl_status llamarl_offpolicy_loss_bwd_slice(const void* H, const void* W_slice, const int32_t* targets,
@@ -516,7 +559,7 @@ llamarl_status llamarl_offpolicy_loss_bwd_slice(const void* H, const void* W_sli
                                                 void* dH_partial, void* dW_slice, llamarl_dtype dW_dt,
                                                 int accumulate_dW, void* ws, size_t ws_bytes, void* stream) {
   return bwd_entry(H, W_slice, targets, lse, coef, grad_loss, N, d, V_slice, v0, dt, dH_partial, dW_slice, dW_dt,
-                   accumulate_dW, ws, ws_bytes, stream, nullptr);
+                   accumulate_dW, 0, ws, ws_bytes, stream, nullptr);
 }
 
 llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, const int32_t* targets,
@@ -527,7 +570,7 @@ llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, c
   if (!phase_events) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events is null");
   for (int i = 0; i < 6; ++i)
     if (!phase_events[i]) return fail(LLAMARL_ERR_INVALID_ARG, "phase_events[%d] is null", i);
-  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, ws, ws_bytes,
+  return bwd_entry(H, W, targets, lse, coef, grad_loss, N, d, V, 0, dt, dH, dW, dW_dt, accumulate_dW, 0, ws, ws_bytes,
                    stream, phase_events);
 }
 

@@ -178,6 +178,46 @@ def test_dW_fp32_output_and_accumulation(lib):
     assert first.dtype == torch.bfloat16
 
 
+@pytest.mark.parametrize("w", [
+    synth.scaled(W8, d=264, V=3001, B=3, T=347, len_lo=100, len_hi=300, seed=61),
+    synth.scaled(W1, d=132, V=900, B=3, T=300, len_lo=100, len_hi=250, seed=62),
+], ids=["bf16", "f32"])
+def test_backward_in_row_passes_with_a_bounded_workspace(lib, w):
+    # the active rows are taken 256 at a time: dz is staged for 256 rows only, every pass adds its share to dW;
+    # the batch has more 256-row passes than active rows, so the last passes find nothing to do
+    x = synth.make_inputs(w, "cuda")
+    N, d, V = w.N, w.d, w.V
+    dt = lib.BF16 if w.dtype == "bf16" else lib.F32
+    ref = run_oracle(x)
+    one = run_hip(lib, x, dW_dtype=torch.float32)
+    n_act = int((one["coef"] != 0).sum())
+    assert 512 < n_act and (N + 255) // 256 > (n_act + 255) // 256
+    small, whole = lib.bwd_workspace_bytes(N, d, V, dt, 256), lib.workspace_bytes(N, d, V, dt, lib.PASS_LOSS_BWD)
+    assert small < 0.45 * whole and lib.bwd_workspace_bytes(N, d, V, dt, 0) == whole
+    ws = torch.full((small,), 0xFF, dtype=torch.uint8, device="cuda")
+    for dW_dtype in (torch.float32, x["H"].dtype):
+        dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], one["lse"], one["coef"], dW_dtype=dW_dtype,
+                                        ws=ws, max_rows_per_pass=256)
+        torch.cuda.synchronize()
+        check_grad("dH (row passes)", f64(dH), ref["dH"], w.dtype)
+        check_grad("dW (row passes)", f64(dW), ref["dW"], w.dtype)
+        assert torch.equal(dH, one["dH"])                  # a dH row belongs to one pass: same contraction, same bits
+        if dW_dtype == torch.float32:
+            assert torch.allclose(dW, one["dW"], rtol=0, atol=2e-6 * float(one["dW"].abs().max()))
+    # accumulate_dW holds for the first pass too
+    dW2 = dW.clone()
+    lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], one["lse"], one["coef"], dW=dW2, accumulate_dW=True, ws=ws,
+                           max_rows_per_pass=256)
+    torch.cuda.synchronize()
+    check_grad("dW (row passes, accumulated twice)", f64(dW2), 2 * ref["dW"], w.dtype)
+    # an all-masked batch: every pass is empty, dW is still written (zeros)
+    dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], one["lse"], torch.zeros_like(one["coef"]),
+                                    dH=torch.full_like(x["H"], float("nan")), dW=torch.full_like(x["W"], float("nan")),
+                                    ws=ws, max_rows_per_pass=256)
+    torch.cuda.synchronize()
+    assert not bool(dH.any()) and not bool(dW.any())
+
+
 def test_masked_rows_with_nan_do_not_leak(lib):
     w = synth.scaled(W8, d=128, V=600, B=3, T=200, len_lo=20, len_hi=150)
     x = synth.make_inputs(w, "cuda")
