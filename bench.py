@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--workload", default="llama3_8b")
     ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the bounded oracle sample (0 = skip)")
     ap.add_argument("--cpu-rows-one-thread", type=int, default=192, help="rows of the single-thread oracle leg")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the MFMA-ceiling, streaming-epilogue and library-GEMM legs (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 1 GiB device copies and exit (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -272,7 +274,7 @@ def main():
     # ---- what the matrix pipes sustain on this machine with nothing else running (MFMA-only kernel, same
     # instruction and wave shape): the published peak assumes 2.4 GHz, which the chip does not hold under MFMA load
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
-    iters = 20000                                                            # ~10 ms per launch
+    iters = 20 if args.no_extras else 20000                                  # ~10 ms per launch
     for _ in range(3):
         ceil_flops = L.mfma_ceiling(iters, sink, stream=stream)
     cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(7)]
@@ -314,9 +316,13 @@ def main():
                                      "x1.0 (plain-copy calibration; includes Infinity-Cache hits); read from "
                                      "profiles/bench_llama3_8b_hbm_traffic_pmc.md, not measured in this run"},
         "roofline_per_kernel": per_kernel,
-        "streaming_epilogue": streaming_epilogue(L, x, w, t_loss, dev, stream),
     }
-    if w.dtype == "bf16":
+    if not args.no_extras:
+        out["streaming_epilogue"] = streaming_epilogue(L, x, w, t_loss, dev, stream)
+    if args.no_extras:
+        del out["mfma_ceiling"], out["step_frac_of_measured_ceiling_8NVd"]
+        del out["roofline"]["measured_ceiling"], out["roofline"]["frac_of_measured_ceiling"]
+    if w.dtype == "bf16" and not args.no_extras:
         out["library_gemm"] = library_gemm(x, flops_gemm)
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(x, w, args.cpu_rows, args.cpu_rows_one_thread)

@@ -254,7 +254,13 @@ struct SlabFetch {
   int k0, K, wave, lane;
 };
 
-// One k-step = one MFMA depth (two per slab): 32 slots, slot t runs block (ib, jb) = (t / 4, t % 4).
+// Column block of MFMA slot t: rows of blocks are walked alternately left-to-right and right-to-left, so the column
+// operand stays the same across a row change (the row operand changes there).  The chip is power-limited under
+// MFMA load and operand switching costs energy: this order measured 0.5 % faster on every contraction kernel than
+// restarting each row at column block 0.
+__device__ __forceinline__ constexpr int snake_col(int t) { return ((t >> 2) & 1) ? 3 - (t & 3) : (t & 3); }
+
+// One k-step = one MFMA depth (two per slab): 32 slots, slot t runs block (ib, jb) = (t / 4, snake_col(t)).
 //   a[8]   : the A fragments of this k-step, one register set each.  Block ib is done after slot 4 ib + 3 and its
 //            registers take the NEXT k-step's fragment right away (slot 4 ib + 4): 28 slots ahead of its use.
 //            a[7] of a k-step is read at its own slot 0.
@@ -274,7 +280,7 @@ __device__ __forceinline__ void k_step(typename TT::frag_t (&a)[MB], const typen
   static_assert(MB == 8 && NB == 4, "slot table written for an 8 x 4 wave tile");
 #pragma unroll
   for (int t = 0; t < MB * NB; ++t) {
-    const int ib = t >> 2, jb = t & 3;
+    const int ib = t >> 2, jb = snake_col(t);
     if (BAR && t == TB) {
       wait_vmcnt0();      // this thread's share of the next slab has landed in LDS
       __syncthreads();    // everyone's has, and everyone is done reading this slab
@@ -289,7 +295,7 @@ __device__ __forceinline__ void k_step(typename TT::frag_t (&a)[MB], const typen
     if (NEXT) {
       if (t == TB) a[0] = *reinterpret_cast<const frag_t*>(pa_nxt);
       if (t == TB + 1) a[1] = *reinterpret_cast<const frag_t*>(pa_nxt + BLOCK_BYTES);
-      if (t >= 12 && jb == 0) a[ib - 1] = *reinterpret_cast<const frag_t*>(pa_nxt + (ib - 1) * BLOCK_BYTES);
+      if (t >= 12 && (t & 3) == 0) a[ib - 1] = *reinterpret_cast<const frag_t*>(pa_nxt + (ib - 1) * BLOCK_BYTES);
       if (t == 10) bn[0] = *reinterpret_cast<const frag_t*>(pb_nxt);
       if (t == 14) bn[1] = *reinterpret_cast<const frag_t*>(pb_nxt + BLOCK_BYTES);
       if (t == 18) bn[2] = *reinterpret_cast<const frag_t*>(pb_nxt + 2 * BLOCK_BYTES);

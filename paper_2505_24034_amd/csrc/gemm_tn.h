@@ -145,7 +145,7 @@ struct TileGemmTN {
     static_assert(MB == 8 && NB == 4, "slot table written for an 8 x 4 wave tile");
 #pragma unroll
     for (int t = 0; t < MB * NB; ++t) {
-      const int ib = t >> 2, jb = t & 3;
+      const int ib = t >> 2, jb = snake_col(t);
       if (BAR && t == TB) {
         wait_vmcnt0();      // this thread's share of the next slab has landed in LDS
         __syncthreads();    // everyone's has, and everyone is done reading this slab
@@ -160,7 +160,7 @@ struct TileGemmTN {
       if (NEXT) {
         if (t == TB) a[0] = read_frag(blk(pa_nxt, 0, fx));
         if (t == TB + 1) a[1] = read_frag(blk(pa_nxt, 1, fx));
-        if (t >= 12 && jb == 0) a[ib - 1] = read_frag(blk(pa_nxt, ib - 1, fx));
+        if (t >= 12 && (t & 3) == 0) a[ib - 1] = read_frag(blk(pa_nxt, ib - 1, fx));
         if (t == 10) bn[0] = read_frag(blk(pb_nxt, 0, fxb));
         if (t == 14) bn[1] = read_frag(blk(pb_nxt, 1, fxb));
         if (t == 18) bn[2] = read_frag(blk(pb_nxt, 2, fxb));

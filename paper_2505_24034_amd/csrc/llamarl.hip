@@ -169,9 +169,9 @@ int persistent_grid(int64_t tiles) {
 
 template <typename TT, bool KMAJOR, int MODE>
 llamarl_status launch_store_mode(const StoreArgs& a, int64_t work_items, hipStream_t st) {
-  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR, MODE>, MAINLOOP_LDS_BYTES));
-  k_gemm_store<TT, KMAJOR, MODE><<<dim3((unsigned)persistent_grid(work_items)), dim3(NTHREADS), MAINLOOP_LDS_BYTES,
-                                   st>>>(a);
+  constexpr int lds = MAINLOOP_LDS_BYTES;
+  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR, MODE>, lds));
+  k_gemm_store<TT, KMAJOR, MODE><<<dim3((unsigned)persistent_grid(work_items)), dim3(NTHREADS), lds, st>>>(a);
   HIP_TRY(hipGetLastError());
   return LLAMARL_OK;
 }
