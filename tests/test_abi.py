@@ -128,3 +128,49 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libllamarl.so")
     with pytest.raises(binding.LlamarlError):
         binding.load()
+
+
+def test_bounded_backward_workspace_sizes(clib):
+    bw = binding.bwd_workspace_bytes
+    N, d, V = 16384, 4096, 128256
+    whole = binding.workspace_bytes(N, d, V, binding.BF16, binding.PASS_LOSS_BWD)
+    assert bw(N, d, V, binding.BF16, 0) == whole == bw(N, d, V, binding.BF16, N) == bw(N, d, V, binding.BF16, 10 ** 9)
+    capped = bw(N, d, V, binding.BF16, 8704)
+    assert V * 8704 * 2 <= capped < 0.56 * whole                 # dz^T for 8704 rows instead of 16384
+    assert bw(N, d, V, binding.BF16, 300) == bw(N, d, V, binding.BF16, 512)      # rounded up to whole 256-row tiles
+    assert bw(N, d, V, binding.BF16, -1) == 0 and bw(0, d, V, binding.BF16, 256) == 0 and bw(N, d, V, 9, 256) == 0
+
+
+@no_gpu_only
+def test_new_entry_points_reject_bad_arguments(clib):
+    vp = ctypes.c_void_p
+    fake = lambda i: vp(1 << (20 + i))
+    # vocabulary shard outside the head
+    st = clib.llamarl_token_logprobs_partial(fake(0), fake(1), fake(2), None, 16, 8, 8, 4, 10, binding.BF16, fake(3),
+                                             fake(4), fake(5), fake(6), 1 << 30, None)
+    assert st == binding.ERR_INVALID_ARG and b"slice" in clib.llamarl_last_error()
+    st = clib.llamarl_token_logprobs_partial(fake(0), fake(1), fake(2), None, 16, 8, 8, 0, 8, binding.BF16, fake(3),
+                                             fake(4), None, fake(6), 1 << 30, None)
+    assert st == binding.ERR_INVALID_ARG
+    assert clib.llamarl_merge_partials(fake(0), fake(1), fake(2), 0, 16, fake(3), fake(4), None) == binding.ERR_INVALID_ARG
+    assert clib.llamarl_merge_partials(fake(0), None, fake(2), 2, 16, fake(3), fake(4), None) == binding.ERR_INVALID_ARG
+    st = clib.llamarl_offpolicy_loss_bwd_slice(fake(0), fake(1), fake(2), fake(3), fake(4), 1.0, 16, 8, 8, -1,
+                                               binding.BF16, fake(5), fake(6), binding.BF16, 0, fake(7), 1 << 30, None)
+    assert st == binding.ERR_INVALID_ARG
+    st = clib.llamarl_offpolicy_loss_bwd_chunked(fake(0), fake(1), fake(2), fake(3), fake(4), 1.0, 16, 8, 8,
+                                                 binding.BF16, fake(5), fake(6), binding.BF16, 0, -5, fake(7), 1 << 30,
+                                                 None)
+    assert st == binding.ERR_INVALID_ARG and b"max_rows_per_pass" in clib.llamarl_last_error()
+    st = clib.llamarl_offpolicy_loss_bwd_chunked(fake(0), fake(1), fake(2), fake(3), fake(4), 1.0, 1024, 64, 512,
+                                                 binding.BF16, fake(5), fake(6), binding.BF16, 0, 256, fake(7), 1000, None)
+    assert st == binding.ERR_WORKSPACE
+    # the static-scratch loss: size limits and misaligned inputs are refused before any HIP call
+    p = binding.LossParams(2.0, 0, 0.2, 0.2, 0)
+    st = clib.llamarl_offpolicy_loss_fwd_static(fake(0), fake(1), fake(2), 0, None, None, 0, 2, (1 << 21) + 1,
+                                                ctypes.byref(p), fake(3), fake(4), fake(5), None)
+    assert st == binding.ERR_UNSUPPORTED and b"static scratch" in clib.llamarl_last_error()
+    st = clib.llamarl_offpolicy_loss_fwd_static(vp((1 << 20) + 4), fake(1), fake(2), 0, None, None, 0, 2, 8,
+                                                ctypes.byref(p), fake(3), fake(4), fake(5), None)
+    assert st == binding.ERR_INVALID_ARG and b"aligned" in clib.llamarl_last_error()
+    flops = ctypes.c_double()
+    assert clib.llamarl_mfma_ceiling(0, fake(0), ctypes.byref(flops), None) == binding.ERR_INVALID_ARG
