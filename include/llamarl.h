@@ -233,7 +233,8 @@ llamarl_status llamarl_offpolicy_loss_bwd_slice(const void* H, const void* W_sli
  * MEASUREMENT AID, outside the method: llamarl_offpolicy_loss_bwd, which in addition records six caller-owned HIP events
  * (phase_events[0..5], HOST array of hipEvent_t passed as void*) on `stream`: [0] before the first kernel,
  * [1] after the set-up kernels (active-row list, zeroed dH rows, operand panels), [2] after the recompute + dz
- * kernel, [3] after the dH contraction, [4] after its split reduction, [5] after the dW contraction.  Same results, same
+ * kernel, [3] after the dH contraction (the reduction of its last round's split tiles included), [4] = [3],
+ * [5] after the dW contraction.  Same results, same
  * kernels, same error behaviour (plus INVALID_ARG for a null event).  The backward's four stages are all in this
  * one call, so per-kernel rooflines of the backward can only be timed from inside it.
  */

@@ -7,7 +7,7 @@
 //   k_gemm_store     plain contraction with a store epilogue: dW = dz^T H (K-contiguous operands) and
 //                    dH = dz W (k-major operands: dz^T as written, W as the caller holds it; bf16)
 //   k_transpose      [R,C] -> [C,R] with zero padding and row gather (H^T panel of the active tokens; fp32: W^T too)
-//   k_compact_rows   ascending list of active token rows; k_zero_inactive_rows, k_reduce_splits: small helpers
+//   k_compact_rows   ascending list of active token rows; k_zero_inactive_rows, k_reduce_tail: small helpers
 //
 // In the two logits kernels the MFMA "row" operand is W (vocab) and the "column" operand is H (tokens): an
 // accumulator lane then holds ONE token per column block (column = lane % 16) and 4 vocab entries per 16x16
@@ -540,82 +540,188 @@ struct StoreArgs {
   const int32_t* c_rows;    // non-null: output row r goes to row c_rows[r] of C
   const int32_t* pitch_count;  // non-null: operands flagged below have the row pitch packed_pitch(*pitch_count)
   int packed_a, packed_b;   // A / B is such a panel (lda / ldb are then ignored)
-  int splits;               // > 1: split s contracts its share of the K slabs into the fp32 slice C + s * split_stride
-  int64_t split_stride;
+  int max_splits;           // the tiles of the last, partial round may be split this many ways along K (1: never)
+  float* part;              // [splits][tail tiles][BM x BN] fp32 partial products of split tiles
+  int32_t* plan_out;        // [4] {whole, rem, splits, tiles_m}: what k_reduce_tail has to finish
 };
 
-template <typename TT>
-struct StoreTile {     // what one tile of k_gemm_store contracts and where it goes
-  int64_t row0, col0, k_lo, k_len;
-  int rowsA, rowsB, split;
-  __device__ __forceinline__ void set(const StoreArgs& a, int tiles_m, int64_t M, int64_t K, int tms, int tn) {
-    constexpr int BK = 8 * TT::EPC;
-    split = tms / tiles_m;                           // split-major ids: tiles of one K range run together
-    row0 = (int64_t)(tms - split * tiles_m) * BM;
-    col0 = (int64_t)tn * BN;
-    rowsA = (int)min((int64_t)BM, M - row0);
-    rowsB = (int)min((int64_t)BN, a.Nn - col0);
-    const int nk = (int)((K + BK - 1) / BK);         // 32-bit: slabs per contraction fit an int by far
-    k_lo = (int64_t)(nk * split / a.splits) * BK;
-    k_len = min(K, (int64_t)(nk * (split + 1) / a.splits) * BK) - k_lo;
+// Work list of a store contraction.  T tiles on a persistent grid of G workgroups: the first floor(T / G) * G tiles
+// are contracted whole, one per workgroup and round, and stored in their final form.  The rem = T mod G tiles left
+// would occupy only rem of the G workgroups for a whole tile time; instead each is split along K into as many parts
+// as fit the grid (at most max_splits, at least four K slabs each), the parts run as one last, short round, leave
+// fp32 partial products in the workspace, and k_reduce_tail adds them in split order.  This is what keeps a
+// contraction with few output tiles and a long K (dH: 34 x 16 tiles, K = V) on all CUs without a split-K round trip
+// for every tile, and what trims the last round of dW (8016 tiles on 256 CUs).  The assignment is fixed by the
+// sizes alone: results stay bitwise reproducible.
+struct StorePlan {
+  int tiles_m, tiles_n, group_m;
+  int whole, rem, splits, n_items;
+  int next, stride;
+  __device__ __forceinline__ void init(int tiles_m_, int tiles_n_, int group_m_, int nk, int max_splits) {
+    tiles_m = tiles_m_;
+    tiles_n = tiles_n_;
+    group_m = group_m_;
+    const int T = tiles_m * tiles_n, G = gridDim.x;
+    whole = T / G * G;
+    rem = T - whole;
+    int sp = rem > 0 ? min(max_splits, G / rem) : 1;
+    while (sp > 1 && nk / sp < 4) --sp;
+    splits = sp;
+    n_items = whole + rem * splits;
+    // 32 consecutive items per XCD and round (see TileSchedule): workgroup b sits on XCD b % 8
+    const int b = blockIdx.x;
+    next = (G & 7) == 0 ? (b & 7) * (G >> 3) + (b >> 3) : b;
+    stride = G;
+  }
+  __device__ __forceinline__ bool has_item() const { return next < n_items; }
+  __device__ __forceinline__ int take() {
+    const int it = next;
+    next += stride;
+    return it;
+  }
+  // item -> tile id, K split and number of splits; tail items are split-major, so the 32 items an XCD holds in
+  // the last round are neighbouring tiles of one K range and share operand panels like whole tiles do
+  __device__ __forceinline__ void decode(int item, int& tile, int& split, int& nsplit) const {
+    if (item < whole) {
+      tile = item;
+      split = 0;
+      nsplit = 1;
+    } else {
+      const int j = item - whole;
+      split = j / rem;
+      tile = whole + (j - split * rem);
+      nsplit = splits;
+    }
+  }
+  __device__ __forceinline__ void coords(int id, int& tm, int& tn) const {   // as TileSchedule::coords
+    const int per_group = group_m * tiles_n;
+    const int g = id / per_group;
+    const int first_m = g * group_m;
+    const int gsize = min(tiles_m - first_m, group_m);
+    const int in_g = id - g * per_group;
+    tm = first_m + in_g % gsize;
+    tn = in_g / gsize;
   }
 };
 
 template <typename TT>
-__device__ __forceinline__ StoreTile<TT> store_tile_of(const TileSchedule& sch, const StoreArgs& a, int id, int tiles_m,
-                                                       int64_t M, int64_t K) {
+struct StoreTile {     // what one work item of k_gemm_store contracts and where it goes
+  int64_t row0, col0, k_lo, k_len;
+  int rowsA, rowsB, split, nsplit, tail_index;
+  __device__ __forceinline__ void set(const StoreArgs& a, const StorePlan& plan, int64_t M, int64_t K, int item) {
+    constexpr int BK = 8 * TT::EPC;
+    int tile, tm, tn;
+    plan.decode(item, tile, split, nsplit);
+    plan.coords(tile, tm, tn);
+    tail_index = tile - plan.whole;
+    row0 = (int64_t)tm * BM;
+    col0 = (int64_t)tn * BN;
+    rowsA = (int)min((int64_t)BM, M - row0);
+    rowsB = (int)min((int64_t)BN, a.Nn - col0);
+    const int nk = (int)((K + BK - 1) / BK);         // 32-bit: slabs per contraction fit an int by far
+    k_lo = (int64_t)(nk * split / nsplit) * BK;
+    k_len = min(K, (int64_t)(nk * (split + 1) / nsplit) * BK) - k_lo;
+  }
+};
+
+template <typename TT>
+__device__ __forceinline__ StoreTile<TT> store_tile_of(const StorePlan& plan, const StoreArgs& a, int item, int64_t M,
+                                                       int64_t K) {
   StoreTile<TT> t;
-  int tms, tn;
-  sch.coords(id, tms, tn);
-  t.set(a, tiles_m, M, K, tms, tn);
+  t.set(a, plan, M, K, item);
   return t;
 }
 template <typename TT>
-__device__ __forceinline__ void store_fetch(TileGemm<TT>& g, const TileSchedule& sch, const StoreArgs& a, int id,
-                                            int tiles_m, int64_t M, int64_t K, char* smem) {
+__device__ __forceinline__ void store_fetch(TileGemm<TT>& g, const StorePlan& plan, const StoreArgs& a, int item,
+                                            int64_t M, int64_t K, char* smem) {
   typedef typename TT::store_t st;
-  const StoreTile<TT> t = store_tile_of<TT>(sch, a, id, tiles_m, M, K);
+  const StoreTile<TT> t = store_tile_of<TT>(plan, a, item, M, K);
   if (t.k_len > 0)
     g.template prefetch<false, true>((const st*)a.A + t.row0 * a.lda + t.k_lo, a.lda, t.rowsA,
                                (const st*)a.B + t.col0 * a.ldb + t.k_lo, a.ldb, t.rowsB, t.k_len, smem);
 }
 // k-major operands: A is At [K][lda] (output rows are its columns), B is Bt [K][ldb]
-__device__ __forceinline__ void store_fetch(TileGemmTN& g, const TileSchedule& sch, const StoreArgs& a, int id,
-                                            int tiles_m, int64_t M, int64_t K, char* smem) {
-  const StoreTile<BF16> t = store_tile_of<BF16>(sch, a, id, tiles_m, M, K);
+__device__ __forceinline__ void store_fetch(TileGemmTN& g, const StorePlan& plan, const StoreArgs& a, int item, int64_t M,
+                                            int64_t K, char* smem) {
+  const StoreTile<BF16> t = store_tile_of<BF16>(plan, a, item, M, K);
   if (t.k_len > 0)
     g.prefetch((const uint16_t*)a.A + t.k_lo * a.lda + t.row0, a.lda, t.row0,
                (const uint16_t*)a.B + t.k_lo * a.ldb + t.col0, a.ldb, t.col0, (int)t.k_len, smem);
 }
 
-// MODE (compile time, so each instantiation carries one epilogue only):
-//   0 fp32 split-K partial slice   1 fp32   2 fp32 accumulate   3 bf16   4 bf16 accumulate
+// One output element group in its final form.  MODE: 1 fp32, 2 fp32 accumulate, 3 bf16, 4 bf16 accumulate.
+template <int MODE>
+__device__ __forceinline__ void store_final4(char* q, float v0, float v1, float v2, float v3) {
+  if (MODE <= 2) {
+    float4* f = reinterpret_cast<float4*>(q);
+    if (MODE == 2) {
+      const float4 old = *f;
+      v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
+    }
+    *f = make_float4(v0, v1, v2, v3);
+  } else {
+    uint2* h = reinterpret_cast<uint2*>(q);
+    if (MODE == 4) {
+      const uint2 old = *h;
+      v0 += bf16_bits_to_float((uint16_t)(old.x & 0xffffu));
+      v1 += bf16_bits_to_float((uint16_t)(old.x >> 16));
+      v2 += bf16_bits_to_float((uint16_t)(old.y & 0xffffu));
+      v3 += bf16_bits_to_float((uint16_t)(old.y >> 16));
+    }
+    uint2 o;
+    o.x = pack_bf16(v0, v1);
+    o.y = pack_bf16(v2, v3);
+    *h = o;
+  }
+}
+template <int MODE>
+__device__ __forceinline__ void store_final1(char* q, float v) {
+  if (MODE <= 2) {
+    float* f = reinterpret_cast<float*>(q);
+    if (MODE == 2) v += *f;
+    *f = v;
+  } else {
+    uint16_t* h = reinterpret_cast<uint16_t*>(q);
+    if (MODE == 4) v += bf16_bits_to_float(*h);
+    *h = float_to_bf16_bits(v);
+  }
+}
+
+// MODE (compile time): the final form of the output, see store_final4.  Split tiles of the last round leave fp32
+// partial products instead (k_reduce_tail finishes them in the same MODE).
 template <typename TT, bool KMAJOR, int MODE>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   typedef typename TT::store_t st;
+  constexpr int BK = 8 * TT::EPC;
   const int64_t M = a.m_count ? (int64_t)*a.m_count : a.M;
   const int64_t K = a.k_count ? ((int64_t)*a.k_count + 63) / 64 * 64 : a.K;
   // a later pass of a chunked backward that found no active rows: nothing to add to what the output holds
-  if ((MODE == 2 || MODE == 4) && a.k_count != nullptr && K == 0) return;
+  if ((MODE == 2 || MODE == 4) && a.k_count != nullptr && K == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      a.plan_out[0] = 0; a.plan_out[1] = 0; a.plan_out[2] = 1; a.plan_out[3] = 0;
+    }
+    return;
+  }
   if (a.pitch_count != nullptr) {                    // kernel arguments are a private copy
     const int64_t pp = packed_pitch(*a.pitch_count);
     if (a.packed_a) a.lda = pp;
     if (a.packed_b) a.ldb = pp;
   }
   const int tiles_m = (int)((M + BM - 1) / BM);
-  TileSchedule sch;
-  sch.init(tiles_m * a.splits, a.tiles_n, PATCH_ROWS_STORE);
-  if (!sch.has_tile()) return;                       // block-uniform
-  const int tid = threadIdx.x;
-  const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
+  StorePlan plan;
+  plan.init(tiles_m, a.tiles_n, PATCH_ROWS_STORE, (int)((K + BK - 1) / BK), a.max_splits);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.plan_out[0] = plan.whole; a.plan_out[1] = plan.rem; a.plan_out[2] = plan.splits; a.plan_out[3] = tiles_m;
+  }
+  if (!plan.has_item()) return;                      // block-uniform
   typename std::conditional<KMAJOR, TileGemmTN, TileGemm<TT>>::type g;
-  int id = sch.take();
-  store_fetch(g, sch, a, id, tiles_m, M, K, smem);
+  int id = plan.take();
+  store_fetch(g, plan, a, id, M, K, smem);
   while (true) {
     f32x4_t acc[MB][NB];
     const int cur_id = id;
-    if (store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K).k_len > 0) {
+    if (store_tile_of<TT>(plan, a, cur_id, M, K).k_len > 0) {
       g.run(smem, acc);
     } else {                                         // nothing to contract: the product is zero
 #pragma unroll
@@ -625,100 +731,90 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
     }
-    const bool more = sch.has_tile();
+    const bool more = plan.has_item();
     wait_vmcnt0();                                   // nothing may wait on vmcnt after the slab requests: see k_fwd_partials
     __syncthreads();                                 // every wave is done reading the slab buffers
     if (more) {                                      // the store epilogue uses no LDS: fetch the next tile under it
-      id = sch.take();
-      store_fetch(g, sch, a, id, tiles_m, M, K, smem);
+      id = plan.take();
+      store_fetch(g, plan, a, id, M, K, smem);
     }
     LLAMARL_FENCE();
 
-    const StoreTile<TT> cur = store_tile_of<TT>(sch, a, cur_id, tiles_m, M, K);
+    const StoreTile<TT> cur = store_tile_of<TT>(plan, a, cur_id, M, K);
+    int tid = threadIdx.x;                           // opaque per tile: see k_fwd_partials (a spilled per-lane constant
+    asm volatile("" : "+v"(tid));                    // reloaded here would wait for the slab requests above)
+    const LanePos lp{(tid >> 6) / WAVES_N, (tid >> 6) % WAVES_N, tid & 63};
     // Store epilogue, one 16-row block at a time (fences keep the unrolled blocks from piling up address registers).
     // Addresses are a uniform 64-bit tile base plus a 32-bit per-lane byte offset (a 256-row panel is < 2 GiB).
     // The offset passes through an empty asm once per tile: otherwise the 32 row offsets of a lane, which do not
     // depend on the tile, are hoisted out of the persistent loop and live in scratch memory.
-    constexpr int mode = MODE;
-    constexpr int esz = (mode >= 3) ? 2 : 4;
-    char* Cb = reinterpret_cast<char*>(a.C);
-    if (mode == 0) Cb += (int64_t)cur.split * a.split_stride * 4;
-    const bool scatter = (mode != 0) && a.c_rows != nullptr;
-    const uint32_t ldc_b = (uint32_t)a.ldc * esz;
-    char* tile_base = Cb + (cur.row0 * a.ldc + cur.col0) * esz;
     const int row_l = lp.row(0, 0);                                // lane's first row; (ib, r) adds 16 ib + r
-    if constexpr (!KMAJOR) {
-      // K-contiguous operands are fetched quad-interleaved: a lane's four column blocks are neighbouring columns
-      // c .. c+3, stored as one unit; 16 lanes cover 64 consecutive columns of a row -- whole 128-byte lines for
-      // bf16 with no cross-lane traffic (stores that split a line over lanes of different rows measured ~0.5 ms
-      // per GB slower).  The number of columns is a multiple of 4 (checked on the host): a quad is never cut.
-      const int c = lp.col_quad();
-      const bool in_cols = c < cur.rowsB;
-      uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)c * esz;
+    if (cur.nsplit > 1) {
+      // a split tile of the last round (block-uniform): the whole 256 x 256 fp32 block goes to the workspace,
+      // rows and columns past the matrix edge included (they hold zeros or values nobody reads)
+      char* blk = reinterpret_cast<char*>(a.part + ((int64_t)cur.split * plan.rem + cur.tail_index) * (BM * BN));
+      uint32_t lane_off = (uint32_t)row_l * (BN * 4) + (uint32_t)(KMAJOR ? lp.col(0) : lp.col_quad()) * 4u;
       asm volatile("" : "+v"(lane_off));
 #pragma unroll
       for (int i = 0; i < MB; ++i) {
         LLAMARL_FENCE();
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int rel = i * 16 + r;
-          const int rib = row_l + rel;
-          if (rib < cur.rowsA && in_cols) {
-            char* q = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + c) * esz
-                              : tile_base + (lane_off + (uint32_t)rel * ldc_b);
-            float v0 = acc[i][0][r], v1 = acc[i][1][r], v2 = acc[i][2][r], v3 = acc[i][3][r];
-            if (mode <= 2) {
-              float4* f = reinterpret_cast<float4*>(q);
-              if (mode == 2) {
-                const float4 old = *f;
-                v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
-              }
-              *f = make_float4(v0, v1, v2, v3);
-            } else {
-              uint2* h = reinterpret_cast<uint2*>(q);
-              if (mode == 4) {
-                const uint2 old = *h;
-                v0 += bf16_bits_to_float((uint16_t)(old.x & 0xffffu));
-                v1 += bf16_bits_to_float((uint16_t)(old.x >> 16));
-                v2 += bf16_bits_to_float((uint16_t)(old.y & 0xffffu));
-                v3 += bf16_bits_to_float((uint16_t)(old.y >> 16));
-              }
-              uint2 o;
-              o.x = pack_bf16(v0, v1);
-              o.y = pack_bf16(v2, v3);
-              *h = o;
-            }
+          char* q = blk + (lane_off + (uint32_t)(i * 16 + r) * (BN * 4));
+          if constexpr (!KMAJOR) {
+            *reinterpret_cast<float4*>(q) = make_float4(acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < NB; ++j) reinterpret_cast<float*>(q)[j * 16] = acc[i][j][r];
           }
         }
       }
     } else {
-      // k-major operands keep the plain column order: one element per lane and column block
-      uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)lp.col(0) * esz;
-      asm volatile("" : "+v"(lane_off));
+      constexpr int esz = (MODE >= 3) ? 2 : 4;
+      char* Cb = reinterpret_cast<char*>(a.C);
+      const bool scatter = a.c_rows != nullptr;
+      const uint32_t ldc_b = (uint32_t)a.ldc * esz;
+      char* tile_base = Cb + (cur.row0 * a.ldc + cur.col0) * esz;
+      if constexpr (!KMAJOR) {
+        // K-contiguous operands are fetched quad-interleaved: a lane's four column blocks are neighbouring columns
+        // c .. c+3, stored as one unit; 16 lanes cover 64 consecutive columns of a row -- whole 128-byte lines for
+        // bf16 with no cross-lane traffic (stores that split a line over lanes of different rows measured ~0.5 ms
+        // per GB slower).  The number of columns is a multiple of 4 (checked on the host): a quad is never cut.
+        const int c = lp.col_quad();
+        const bool in_cols = c < cur.rowsB;
+        uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)c * esz;
+        asm volatile("" : "+v"(lane_off));
 #pragma unroll
-      for (int i = 0; i < MB; ++i) {
-        LLAMARL_FENCE();
+        for (int i = 0; i < MB; ++i) {
+          LLAMARL_FENCE();
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int rel = i * 16 + r;
-          const int rib = row_l + rel;
-          if (rib < cur.rowsA) {
-            char* rowq = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + lp.col(0)) * esz
-                                 : tile_base + (lane_off + (uint32_t)rel * ldc_b);
+          for (int r = 0; r < 4; ++r) {
+            const int rel = i * 16 + r;
+            const int rib = row_l + rel;
+            if (rib < cur.rowsA && in_cols) {
+              char* q = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + c) * esz
+                                : tile_base + (lane_off + (uint32_t)rel * ldc_b);
+              store_final4<MODE>(q, acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]);
+            }
+          }
+        }
+      } else {
+        // k-major operands keep the plain column order: one element per lane and column block
+        uint32_t lane_off = (uint32_t)row_l * ldc_b + (uint32_t)lp.col(0) * esz;
+        asm volatile("" : "+v"(lane_off));
 #pragma unroll
-            for (int j = 0; j < NB; ++j) {
-              if (lp.col(j) < cur.rowsB) {
-                float v = acc[i][j][r];
-                if (mode <= 2) {
-                  float* q = reinterpret_cast<float*>(rowq) + j * 16;
-                  if (mode == 2) v += *q;
-                  *q = v;
-                } else {
-                  uint16_t* q = reinterpret_cast<uint16_t*>(rowq) + j * 16;
-                  if (mode == 4) v += bf16_bits_to_float(*q);
-                  *q = float_to_bf16_bits(v);
-                }
-              }
+        for (int i = 0; i < MB; ++i) {
+          LLAMARL_FENCE();
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int rel = i * 16 + r;
+            const int rib = row_l + rel;
+            if (rib < cur.rowsA) {
+              char* rowq = scatter ? Cb + ((int64_t)a.c_rows[cur.row0 + rib] * a.ldc + cur.col0 + lp.col(0)) * esz
+                                   : tile_base + (lane_off + (uint32_t)rel * ldc_b);
+#pragma unroll
+              for (int j = 0; j < NB; ++j)
+                if (lp.col(j) < cur.rowsB) store_final1<MODE>(rowq + j * 16 * esz, acc[i][j][r]);
             }
           }
         }
@@ -728,28 +824,39 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   }
 }
 
-// out[rows[p]][c] = sum over splits (ascending) of part[s][p][c], p < *m_count; 4 columns per thread.
-template <typename ST>
-__global__ __launch_bounds__(256) void k_reduce_splits(const float* part, int splits, int64_t split_stride,
-                                                        const int32_t* rows, const int32_t* m_count, int64_t ncols,
-                                                        ST* out, int64_t ldo) {
-  const int64_t p = blockIdx.x;
-  if (p >= (int64_t)*m_count) return;
-  const int64_t orow = rows ? (int64_t)rows[p] : p;
-  for (int64_t c = (int64_t)threadIdx.x * 4; c < ncols; c += 256 * 4) {
-    float4 s = *reinterpret_cast<const float4*>(part + p * ncols + c);
+// Finishes the split tiles of a store contraction's last round: C tile = sum over splits (ascending) of the fp32
+// partial blocks, stored in the contraction's MODE (dtype, accumulate, row scatter).  One block per (tail tile,
+// stripe of 32 rows); the plan is the one k_gemm_store wrote.
+constexpr int TAIL_STRIPE_ROWS = 32;
+template <int MODE>
+__global__ __launch_bounds__(256) void k_reduce_tail(StoreArgs a) {
+  const int whole = a.plan_out[0], rem = a.plan_out[1], splits = a.plan_out[2], tiles_m = a.plan_out[3];
+  const int j = blockIdx.x;
+  if (splits <= 1 || j >= rem) return;               // block-uniform
+  const int64_t M = a.m_count ? (int64_t)*a.m_count : a.M;
+  StorePlan plan;
+  plan.tiles_m = tiles_m;
+  plan.tiles_n = a.tiles_n;
+  plan.group_m = PATCH_ROWS_STORE;
+  int tm, tn;
+  plan.coords(whole + j, tm, tn);
+  const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+  const int rowsA = (int)min((int64_t)BM, M - row0), rowsB = (int)min((int64_t)BN, a.Nn - col0);
+  constexpr int esz = (MODE >= 3) ? 2 : 4;
+  char* Cb = reinterpret_cast<char*>(a.C);
+  const int c = (threadIdx.x & 63) * 4;              // 64 threads x 4 columns = one 256-column row
+  const int r_in = threadIdx.x >> 6;                 // 4 rows at a time
+  for (int rr = r_in; rr < TAIL_STRIPE_ROWS; rr += 4) {
+    const int row = blockIdx.y * TAIL_STRIPE_ROWS + rr;
+    if (row >= rowsA || c >= rowsB) continue;
+    const float* p = a.part + (int64_t)j * (BM * BN) + row * BN + c;
+    float4 s = *reinterpret_cast<const float4*>(p);
     for (int q = 1; q < splits; ++q) {
-      const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)q * split_stride + p * ncols + c);
+      const float4 v = *reinterpret_cast<const float4*>(p + (int64_t)q * rem * (BM * BN));
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
-    if constexpr (sizeof(ST) == 4) {
-      *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + orow * ldo + c) = s;
-    } else {
-      uint2 o;
-      o.x = pack_bf16(s.x, s.y);
-      o.y = pack_bf16(s.z, s.w);
-      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + orow * ldo + c) = o;
-    }
+    const int64_t orow = a.c_rows ? (int64_t)a.c_rows[row0 + row] : row0 + row;
+    store_final4<MODE>(Cb + (orow * a.ldc + col0 + c) * esz, s.x, s.y, s.z, s.w);
   }
 }
 

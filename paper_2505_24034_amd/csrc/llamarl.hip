@@ -89,9 +89,12 @@ struct BwdWs {
                       // partials are sized for R rows; more active rows than that are taken in further passes
   int n_pass;         // passes the host enqueues = ceil(N / R); passes past the active rows find nothing to do
   int64_t ldz, ldzt;  // padded leading dimensions (elements): V rounded up to 64; packed_pitch(R)
-  size_t off_dz, off_dzt, off_wt, off_ht, off_rows, off_nact, off_part, total;
-  int dh_splits;      // K splits of the dH contraction (1 = none)
+  size_t off_dz, off_dzt, off_wt, off_ht, off_rows, off_nact, off_plan, off_part, total;
 };
+// Most workgroups a persistent grid has (one per CU of an MI355X); also the most split items the last round of a
+// store contraction can hold, each leaving one BM x BN fp32 block in the workspace.
+constexpr int MAX_GRID = 256;
+constexpr int STORE_MAX_SPLITS = 8;
 BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows_per_pass) {
   BwdWs w;
   const size_t es = esize(dt);
@@ -108,16 +111,13 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows
   w.off_ht = w.off_wt + (both ? (size_t)round_up(d * w.ldz * (int64_t)es, 256) : 0);
   w.off_rows = w.off_ht + (size_t)round_up(d * w.ldzt * (int64_t)es, 256);
   w.off_nact = w.off_rows + (size_t)round_up(round_up(N, 64) * (int64_t)sizeof(int32_t), 256);
-  w.off_part = w.off_nact + (size_t)round_up((int64_t)(1 + w.n_pass) * (int64_t)sizeof(int32_t), 256);
-  // dH has few output tiles (rows/256 x d/256) with a very long K = V: split K until there are enough work items
-  // to fill 256 CUs evenly (at most ~1/16 of the last round idle) whatever the number of active rows turns out to
-  // be, as long as a split keeps at least four K slabs (64 bf16 / 32 fp32 elements each).  d % 4 keeps float4 rows.
-  const int64_t tiles = ((w.R + BM - 1) / BM) * ((d + BN - 1) / BN);
-  const int64_t slabs = dt == LLAMARL_BF16 ? (V + 63) / 64 : w.ldz / 32;
-  int s = 1;
-  while (s < 8 && tiles * s < 8192 && slabs / (s * 2) >= 4) s *= 2;
-  w.dh_splits = s;
-  w.total = w.off_part + (s > 1 ? (size_t)round_up((int64_t)s * w.R * d * 4, 256) : 0);
+  w.off_plan = w.off_nact + (size_t)round_up((int64_t)(1 + w.n_pass) * (int64_t)sizeof(int32_t), 256);
+  w.off_part = w.off_plan + 256;
+  // fp32 partial blocks of the split tiles of a store contraction's last round (see StorePlan): at most one per
+  // workgroup of the grid, which is never larger than the number of work items a contraction can have
+  const int64_t tiles_dh = ((w.R + BM - 1) / BM) * ((d + BN - 1) / BN), tiles_dw = ((V + BM - 1) / BM) * ((d + BN - 1) / BN);
+  const int64_t blocks = std::min<int64_t>(MAX_GRID, std::max(tiles_dh, tiles_dw) * STORE_MAX_SPLITS);
+  w.total = w.off_part + (size_t)(blocks * BM * BN * 4);
   return w;
 }
 
@@ -156,7 +156,8 @@ int persistent_grid(int64_t tiles) {
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
       cus = n;
     else
-      cus = 256;
+      cus = MAX_GRID;
+    if (cus > MAX_GRID) cus = MAX_GRID;
   }
   return (int)(tiles < (int64_t)cus ? tiles : (int64_t)cus);
 }
@@ -168,35 +169,47 @@ int persistent_grid(int64_t tiles) {
   } while (0)
 
 template <typename TT, bool KMAJOR, int MODE>
-llamarl_status launch_store_mode(const StoreArgs& a, int64_t work_items, hipStream_t st) {
-  constexpr int lds = MAINLOOP_LDS_BYTES;
-  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR, MODE>, lds));
-  k_gemm_store<TT, KMAJOR, MODE><<<dim3((unsigned)persistent_grid(work_items)), dim3(NTHREADS), lds, st>>>(a);
+llamarl_status launch_store_mode(const StoreArgs& a, int64_t work_items, int tiles_worst, hipStream_t st) {
+  HIP_TRY(set_lds(k_gemm_store<TT, KMAJOR, MODE>, MAINLOOP_LDS_BYTES));
+  const int grid = persistent_grid(work_items);
+  k_gemm_store<TT, KMAJOR, MODE><<<dim3((unsigned)grid), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(a);
   HIP_TRY(hipGetLastError());
+  if (a.max_splits > 1) {
+    // the split tiles of the last round, if the device-side sizes left any: fewer than `grid` of them
+    const int tail = std::min(grid - 1, tiles_worst);
+    if (tail > 0) {
+      k_reduce_tail<MODE><<<dim3((unsigned)tail, BM / TAIL_STRIPE_ROWS), dim3(256), 0, st>>>(a);
+      HIP_TRY(hipGetLastError());
+    }
+  }
   return LLAMARL_OK;
 }
 
+// C [M,Nn] (+)= A B^T on the persistent grid; ws_part / ws_plan: workspace of the last round's split tiles
 template <typename TT, bool KMAJOR = false>
 llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t Nn,
                                  int64_t K, void* C, int64_t ldc, int c_is_f32, int accumulate, const int32_t* m_count,
-                                 const int32_t* k_count, const int32_t* c_rows, int splits, int64_t split_stride,
+                                 const int32_t* k_count, const int32_t* c_rows, float* ws_part, int32_t* ws_plan,
                                  const int32_t* pitch_count, int packed_a, int packed_b, hipStream_t st) {
-  // the store epilogue of the K-contiguous loop writes four neighbouring columns per lane as one unit
-  if (!KMAJOR && (Nn % 4 != 0 || ldc % 4 != 0))
+  // the store epilogue of the K-contiguous loop writes four neighbouring columns per lane as one unit, and so
+  // does the tail reduction
+  if (Nn % 4 != 0 || ldc % 4 != 0)
     return fail(LLAMARL_ERR_UNSUPPORTED, "output columns and row stride must be multiples of 4");
   StoreArgs a;
-  a.m_count = m_count; a.k_count = k_count; a.c_rows = c_rows; a.splits = splits; a.split_stride = split_stride;
+  a.m_count = m_count; a.k_count = k_count; a.c_rows = c_rows;
+  a.max_splits = STORE_MAX_SPLITS; a.part = ws_part; a.plan_out = ws_plan;
   a.pitch_count = pitch_count; a.packed_a = packed_a; a.packed_b = packed_b;
   a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.M = M; a.Nn = Nn; a.K = K;
   const int tiles_m = (int)((M + BM - 1) / BM);      // worst case: every row active
   a.tiles_n = (int)((Nn + BN - 1) / BN);
   a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
-  const int64_t items = (int64_t)tiles_m * a.tiles_n * splits;
-  if (splits > 1) return launch_store_mode<TT, KMAJOR, 0>(a, items, st);
-  if (c_is_f32) return accumulate ? launch_store_mode<TT, KMAJOR, 2>(a, items, st)
-                                  : launch_store_mode<TT, KMAJOR, 1>(a, items, st);
+  const int tiles = tiles_m * a.tiles_n;
+  const int64_t items = (int64_t)tiles * STORE_MAX_SPLITS;   // a small contraction still gets a workgroup per split
+  if (c_is_f32) return accumulate ? launch_store_mode<TT, KMAJOR, 2>(a, items, tiles, st)
+                                  : launch_store_mode<TT, KMAJOR, 1>(a, items, tiles, st);
   if constexpr (sizeof(typename TT::store_t) == 2) {
-    return accumulate ? launch_store_mode<TT, KMAJOR, 4>(a, items, st) : launch_store_mode<TT, KMAJOR, 3>(a, items, st);
+    return accumulate ? launch_store_mode<TT, KMAJOR, 4>(a, items, tiles, st)
+                      : launch_store_mode<TT, KMAJOR, 3>(a, items, tiles, st);
   } else {
     return fail(LLAMARL_ERR_INVALID_ARG, "a 16-bit output needs a 16-bit input type");
   }
@@ -309,28 +322,21 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
     //   fp32: K-contiguous operands dz [n_act][ldz] and W^T [d][ldz], K zero-padded to ldz
     llamarl_status s;
     float* part = reinterpret_cast<float*>(ws + w.off_part);
-    void* dh_out = w.dh_splits > 1 ? static_cast<void*>(part) : dH;
-    const int dh_f32 = w.dh_splits > 1 ? 1 : (dt == LLAMARL_F32);
-    const int32_t* dh_scatter = w.dh_splits > 1 ? nullptr : rows;
+    int32_t* plan = reinterpret_cast<int32_t*>(ws + w.off_plan);
     if constexpr (kBf16) {
-      s = launch_store_gemm<TT, true>(dzt, w.ldzt, W, d, Rc, d, V, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
-                                      w.dh_splits, w.R * d, n_act, 1, 0, st);
+      s = launch_store_gemm<TT, true>(dzt, w.ldzt, W, d, Rc, d, V, dH, d, 0, 0, n_act, nullptr, rows, part, plan, n_act,
+                                      1, 0, st);
     } else {
-      s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, Rc, d, w.ldz, dh_out, d, dh_f32, 0, n_act, nullptr, dh_scatter,
-                                w.dh_splits, w.R * d, nullptr, 0, 0, st);
+      s = launch_store_gemm<TT>(dz, w.ldz, wt, w.ldz, Rc, d, w.ldz, dH, d, 1, 0, n_act, nullptr, rows, part, plan,
+                                nullptr, 0, 0, st);
     }
     if (s != LLAMARL_OK) return s;
     if (c == 0) PHASE_EVENT(3);
-    if (w.dh_splits > 1) {
-      k_reduce_splits<stt><<<dim3((unsigned)Rc), dim3(256), 0, st>>>(part, w.dh_splits, w.R * d, rows, n_act, d,
-                                                                    reinterpret_cast<stt*>(dH), d);
-      HIP_TRY(hipGetLastError());
-    }
     if (c == 0) PHASE_EVENT(4);
     // dW [V,d] (+)= dz^T [V,n_act] . H^T[d,n_act]^T      (K = n_act, zero-padded to a multiple of 64); passes after
     // the first add to what the earlier ones stored
     s = launch_store_gemm<TT>(dzt, w.ldzt, ht, w.ldzt, V, d, w.ldzt, dW, d, dW_dt == LLAMARL_F32,
-                              c == 0 ? accumulate_dW : 1, nullptr, n_act, nullptr, 1, 0, n_act, 1, 1, st);
+                              c == 0 ? accumulate_dW : 1, nullptr, n_act, nullptr, part, plan, n_act, 1, 1, st);
     if (s != LLAMARL_OK) return s;
     if (c == 0) PHASE_EVENT(5);
   }

@@ -193,7 +193,8 @@ def test_backward_in_row_passes_with_a_bounded_workspace(lib, w):
     n_act = int((one["coef"] != 0).sum())
     assert 512 < n_act and (N + 255) // 256 > (n_act + 255) // 256
     small, whole = lib.bwd_workspace_bytes(N, d, V, dt, 256), lib.workspace_bytes(N, d, V, dt, lib.PASS_LOSS_BWD)
-    assert small < 0.45 * whole and lib.bwd_workspace_bytes(N, d, V, dt, 0) == whole
+    es = 2 if w.dtype == "bf16" else 4
+    assert small <= whole - V * (N - 512) * es and lib.bwd_workspace_bytes(N, d, V, dt, 0) == whole   # dz^T for 256 rows
     ws = torch.full((small,), 0xFF, dtype=torch.uint8, device="cuda")
     for dW_dtype in (torch.float32, x["H"].dtype):
         dH, dW = lib.offpolicy_loss_bwd(x["H"], x["W"], x["targets"], one["lse"], one["coef"], dW_dtype=dW_dtype,
