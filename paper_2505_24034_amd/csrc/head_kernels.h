@@ -865,15 +865,48 @@ __global__ __launch_bounds__(256) void k_reduce_tail(StoreArgs a) {
 // `out` is packed_pitch(R) (ld_out is the pitch the buffer was sized for) and only the first R rounded up to 64
 // columns of `out` are written (the contraction that reads it stops there).
 template <typename ST>
-__global__ void k_transpose(const ST* in, int64_t R, int64_t C, int64_t ld_in, ST* out, int64_t ld_out,
-                            const int32_t* rows, const int32_t* r_count) {
-  __shared__ ST tile[64][65];
+__global__ __launch_bounds__(256) void k_transpose(const ST* in, int64_t R, int64_t C, int64_t ld_in, ST* out,
+                                                    int64_t ld_out, const int32_t* rows, const int32_t* r_count) {
   if (rows != nullptr) {
     R = *r_count;
     ld_out = packed_pitch(R);
   }
   const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
   if (rows != nullptr && r0 >= R) return;                     // block-uniform
+  if constexpr (sizeof(ST) == 2) {
+    // 16-bit elements, whole 16-byte chunks along both matrices' rows (block-uniform test): 16-byte loads and
+    // stores, eight elements a thread, the transposition through LDS in between
+    if (C % 8 == 0 && ld_in % 8 == 0 && ld_out % 8 == 0 && (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+      __shared__ __attribute__((aligned(16))) uint16_t t16[64][72];
+      const int q = threadIdx.x & 7, line = threadIdx.x >> 3;   // 8 chunks x 32 lines, two rounds
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int rr = line + 32 * h;
+        const int64_t r = r0 + rr, c = c0 + q * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r < R && c < C)
+          v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(in) +
+                                              (rows ? (int64_t)rows[r] : r) * ld_in + c);
+        *reinterpret_cast<uint4*>(&t16[rr][q * 8]) = v;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int cc = line + 32 * h;
+        const int64_t c = c0 + cc, r = r0 + q * 8;
+        if (c < C && r < ld_out) {
+          uint32_t w[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            w[j] = (uint32_t)t16[q * 8 + 2 * j][cc] | ((uint32_t)t16[q * 8 + 2 * j + 1][cc] << 16);
+          *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + c * ld_out + r) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+      }
+      return;
+    }
+  }
+  __shared__ ST tile[64][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;     // 256 threads: 64 x 4
   for (int rr = ty; rr < 64; rr += 4) {
     const int64_t r = r0 + rr, c = c0 + tx;
