@@ -33,9 +33,10 @@ __host__ __device__ __forceinline__ int64_t packed_pitch(int64_t n_rows) {
   return ((p & 1) ? p : p + 1) * 64;
 }
 // Patch rows (TileSchedule::init).  Measured at the Llama-3-8B shape with patches dealt round-robin over the XCDs:
-// logits kernels 4 and 8 tie (2: +1 %); dW 8 (4: +1.6 %, 2: +5 %); dH 8 (4 and 16: +1.7 %).
+// logits kernels 4 and 8 tie (2: +1 %); dW 8 (4: +1.6 %, 2: +5 %); dH: see PATCH_ROWS_KMAJOR.
 constexpr int PATCH_ROWS_LOGITS = 4;
 constexpr int PATCH_ROWS_STORE = 8;
+constexpr int PATCH_ROWS_KMAJOR = 16;    // dH on k-major operands, whole tiles of K = V: 16 x 2 (8 x 4: +0.8 %, 4 x 8: +1.7 %)
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -540,6 +541,7 @@ struct StoreArgs {
   const int32_t* c_rows;    // non-null: output row r goes to row c_rows[r] of C
   const int32_t* pitch_count;  // non-null: operands flagged below have the row pitch packed_pitch(*pitch_count)
   int packed_a, packed_b;   // A / B is such a panel (lda / ldb are then ignored)
+  int group_m;              // rows of a 32-tile patch (see TileSchedule)
   int max_splits;           // the tiles of the last, partial round may be split this many ways along K (1: never)
   float* part;              // [splits][tail tiles][BM x BN] fp32 partial products of split tiles
   int32_t* plan_out;        // [4] {whole, rem, splits, tiles_m}: what k_reduce_tail has to finish
@@ -710,7 +712,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
   }
   const int tiles_m = (int)((M + BM - 1) / BM);
   StorePlan plan;
-  plan.init(tiles_m, a.tiles_n, PATCH_ROWS_STORE, (int)((K + BK - 1) / BK), a.max_splits);
+  plan.init(tiles_m, a.tiles_n, a.group_m, (int)((K + BK - 1) / BK), a.max_splits);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     a.plan_out[0] = plan.whole; a.plan_out[1] = plan.rem; a.plan_out[2] = plan.splits; a.plan_out[3] = tiles_m;
   }
@@ -837,7 +839,7 @@ __global__ __launch_bounds__(256) void k_reduce_tail(StoreArgs a) {
   StorePlan plan;
   plan.tiles_m = tiles_m;
   plan.tiles_n = a.tiles_n;
-  plan.group_m = PATCH_ROWS_STORE;
+  plan.group_m = a.group_m;
   int tm, tn;
   plan.coords(whole + j, tm, tn);
   const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
