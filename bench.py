@@ -255,7 +255,6 @@ def main():
     torch.cuda.synchronize()
     t_dz = median([hipev.elapsed_ms(p[1], p[2]) for p in phase])           # k_bwd_dz alone
     t_dh = median([hipev.elapsed_ms(p[2], p[3]) for p in phase])           # dH contraction alone
-    t_red = median([hipev.elapsed_ms(p[3], p[4]) for p in phase])          # its split reduction
     t_dw = median([hipev.elapsed_ms(p[4], p[5]) for p in phase])           # dW contraction alone
     t_setup = median([hipev.elapsed_ms(p[0], p[1]) for p in phase])
     for p in phase:
@@ -264,7 +263,8 @@ def main():
         ("k_fwd_partials (LM-head contraction + online logsumexp; timed as llamarl_token_logprobs, i.e. with "
          "the row compaction and partial merge)", t_lp),
         ("k_bwd_dz (logits recompute + dz)", t_dz),
-        ("k_gemm_store<k-major> (dH = dz W, split-K partials)" if w.dtype == "bf16" else "k_gemm_store (dH)", t_dh),
+        ("k_gemm_store<k-major> (dH = dz W; with the reduction of its last round's split tiles)" if w.dtype == "bf16"
+         else "k_gemm_store (dH)", t_dh),
         ("k_gemm_store (dW = dz^T H)", t_dw),
     ]
     per_kernel = [{"kernel": n, "ms": t, "achieved": flops_gemm / (t * 1e-3) / 1e12, "unit": "TFLOP/s",
@@ -303,7 +303,7 @@ def main():
                          "frac_of_published_peak": ceil_tflops / PEAK_BF16_TFLOPS},
         "step_frac_of_measured_ceiling_8NVd": step_tflops / ceil_tflops,
         "ms_token_logprobs": t_lp, "ms_loss_fwd": t_loss, "ms_loss_bwd": t_bwd,
-        "ms_bwd_setup_kernels": t_setup, "ms_bwd_split_reduce": t_red,
+        "ms_bwd_setup_kernels": t_setup,
         "loss": float(loss.item()), "stats": [float(v) for v in stats.tolist()],
         # the dominant kernel = the slowest of the four contractions, each 2*n_valid*V*d flop per launch
         "roofline": {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["achieved"],

@@ -147,6 +147,8 @@ llamarl_status llamarl_offpolicy_loss_fwd(const float* logp, const float* mu_log
  *     own kernels (no memset node in a captured graph);
  *   - every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads) race.
  *     Calls on one stream, or ordered by events, are fine.  It works on the current device.
+ *   - the first call on a device looks the array's address up (a host-side query, no stream work): make one call
+ *     before capturing a graph.
  */
 llamarl_status llamarl_offpolicy_loss_fwd_static(const float* logp, const float* mu_logp, const float* adv,
                                                  int adv_per_token, const uint8_t* mask, const int32_t* targets,

@@ -36,7 +36,9 @@ __host__ __device__ __forceinline__ int64_t packed_pitch(int64_t n_rows) {
 // logits kernels 4 and 8 tie (2: +1 %); dW 8 (4: +1.6 %, 2: +5 %); dH: see PATCH_ROWS_KMAJOR.
 constexpr int PATCH_ROWS_LOGITS = 4;
 constexpr int PATCH_ROWS_STORE = 8;
-constexpr int PATCH_ROWS_KMAJOR = 16;    // dH on k-major operands, whole tiles of K = V: 16 x 2 (8 x 4: +0.8 %, 4 x 8: +1.7 %)
+// dH on k-major operands, whole tiles of K = V, when the output is at most 16 tiles wide (d <= 4096): 16 x 2
+// patches (8 x 4: +0.8 %, 4 x 8: +1.7 %).  Wider outputs (d = 8192, 16384) keep 8 x 4 (16 x 2: +2 - 3 % there).
+constexpr int PATCH_ROWS_KMAJOR = 16;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));

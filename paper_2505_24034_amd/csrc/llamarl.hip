@@ -198,11 +198,12 @@ llamarl_status launch_store_gemm(const void* A, int64_t lda, const void* B, int6
   StoreArgs a;
   a.m_count = m_count; a.k_count = k_count; a.c_rows = c_rows;
   a.max_splits = STORE_MAX_SPLITS; a.part = ws_part; a.plan_out = ws_plan;
-  a.group_m = KMAJOR ? PATCH_ROWS_KMAJOR : PATCH_ROWS_STORE;
+
   a.pitch_count = pitch_count; a.packed_a = packed_a; a.packed_b = packed_b;
   a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.M = M; a.Nn = Nn; a.K = K;
   const int tiles_m = (int)((M + BM - 1) / BM);      // worst case: every row active
   a.tiles_n = (int)((Nn + BN - 1) / BN);
+  a.group_m = (KMAJOR && a.tiles_n <= 16) ? PATCH_ROWS_KMAJOR : PATCH_ROWS_STORE;
   a.C = C; a.ldc = ldc; a.c_is_f32 = c_is_f32; a.accumulate = accumulate;
   const int tiles = tiles_m * a.tiles_n;
   const int64_t items = (int64_t)tiles * STORE_MAX_SPLITS;   // a small contraction still gets a workgroup per split
