@@ -551,12 +551,13 @@ struct StoreArgs {
 
 // Work list of a store contraction.  T tiles on a persistent grid of G workgroups: the first floor(T / G) * G tiles
 // are contracted whole, one per workgroup and round, and stored in their final form.  The rem = T mod G tiles left
-// would occupy only rem of the G workgroups for a whole tile time; instead each is split along K into as many parts
-// as fit the grid (at most max_splits, at least four K slabs each), the parts run as one last, short round, leave
-// fp32 partial products in the workspace, and k_reduce_tail adds them in split order.  This is what keeps a
+// would occupy only rem of the G workgroups for a whole tile time; instead each is split along K (at most
+// max_splits ways, at least four K slabs each) so that the parts fill the grid in a few short rounds, leave fp32
+// partial products in the workspace, and k_reduce_tail adds them in split order.  This is what keeps a
 // contraction with few output tiles and a long K (dH: 34 x 16 tiles, K = V) on all CUs without a split-K round trip
 // for every tile, and what trims the last round of dW (8016 tiles on 256 CUs).  The assignment is fixed by the
 // sizes alone: results stay bitwise reproducible.
+constexpr int STORE_TAIL_ROUNDS = 4;      // rounds of split parts at the end of a store contraction, at most
 struct StorePlan {
   int tiles_m, tiles_n, group_m;
   int whole, rem, splits, n_items;
@@ -568,9 +569,20 @@ struct StorePlan {
     const int T = tiles_m * tiles_n, G = gridDim.x;
     whole = T / G * G;
     rem = T - whole;
-    int sp = rem > 0 ? min(max_splits, G / rem) : 1;
-    while (sp > 1 && nk / sp < 4) --sp;
-    splits = sp;
+    // split factor of the tail: the one that makes the tail shortest -- ceil(rem s / G) rounds of 1 / s tile time
+    // each -- among those that keep four K slabs per part and at most STORE_TAIL_ROUNDS rounds of parts (each part
+    // leaves a 256 KB block in the workspace); the smallest such factor on ties
+    int best = 1, best_num = 1, best_den = 1;          // tail time best_num / best_den, in tile times
+    for (int sp = 2; sp <= max_splits && rem > 0; ++sp) {
+      const int rounds = (rem * sp + G - 1) / G;
+      if (nk / sp < 4 || rounds > STORE_TAIL_ROUNDS) break;
+      if (rounds * best_den < best_num * sp) {
+        best = sp;
+        best_num = rounds;
+        best_den = sp;
+      }
+    }
+    splits = best;
     n_items = whole + rem * splits;
     // 32 consecutive items per XCD and round (see TileSchedule): workgroup b sits on XCD b % 8
     const int b = blockIdx.x;

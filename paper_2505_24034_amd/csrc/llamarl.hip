@@ -113,10 +113,10 @@ BwdWs bwd_ws(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows
   w.off_nact = w.off_rows + (size_t)round_up(round_up(N, 64) * (int64_t)sizeof(int32_t), 256);
   w.off_plan = w.off_nact + (size_t)round_up((int64_t)(1 + w.n_pass) * (int64_t)sizeof(int32_t), 256);
   w.off_part = w.off_plan + 256;
-  // fp32 partial blocks of the split tiles of a store contraction's last round (see StorePlan): at most one per
-  // workgroup of the grid, which is never larger than the number of work items a contraction can have
+  // fp32 partial blocks of the split tiles at the end of a store contraction (see StorePlan): at most
+  // STORE_TAIL_ROUNDS per workgroup of the grid, and never more than eight per tile
   const int64_t tiles_dh = ((w.R + BM - 1) / BM) * ((d + BN - 1) / BN), tiles_dw = ((V + BM - 1) / BM) * ((d + BN - 1) / BN);
-  const int64_t blocks = std::min<int64_t>(MAX_GRID, std::max(tiles_dh, tiles_dw) * STORE_MAX_SPLITS);
+  const int64_t blocks = std::min<int64_t>((int64_t)STORE_TAIL_ROUNDS * MAX_GRID, std::max(tiles_dh, tiles_dw) * STORE_MAX_SPLITS);
   w.total = w.off_part + (size_t)(blocks * BM * BN * 4);
   return w;
 }

@@ -136,7 +136,7 @@ def test_bounded_backward_workspace_sizes(clib):
     whole = binding.workspace_bytes(N, d, V, binding.BF16, binding.PASS_LOSS_BWD)
     assert bw(N, d, V, binding.BF16, 0) == whole == bw(N, d, V, binding.BF16, N) == bw(N, d, V, binding.BF16, 10 ** 9)
     capped = bw(N, d, V, binding.BF16, 8704)
-    assert V * 8704 * 2 <= capped < 0.56 * whole                 # dz^T for 8704 rows instead of 16384
+    assert V * 8704 * 2 <= capped <= whole - V * (N - 8704 - 128) * 2     # dz^T for 8704 rows instead of 16384
     assert bw(N, d, V, binding.BF16, 300) == bw(N, d, V, binding.BF16, 512)      # rounded up to whole 256-row tiles
     assert bw(N, d, V, binding.BF16, -1) == 0 and bw(0, d, V, binding.BF16, 256) == 0 and bw(N, d, V, 9, 256) == 0
 
