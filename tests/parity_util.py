@@ -47,7 +47,7 @@ def check_grad(name, got, ref, dtype):
     assert err <= 1e-2 * scale + 1e-30, "%s: max |delta| = %.3g vs max |ref| = %.3g" % (name, err, scale)
 
 
-def check_all(got, ref, dtype, check_stats=True):
+def check_all(got, ref, dtype, check_stats=True, f32_loss_scaled=False):
     tol_lp = 1e-4 if dtype == "f32" else 2e-2
     lp, lse = f64(got["logp"]), f64(got["lse"])
     assert np.abs(lp - ref["logp"]).max() <= tol_lp, "logp max |delta| = %.3g" % np.abs(lp - ref["logp"]).max()
@@ -58,7 +58,10 @@ def check_all(got, ref, dtype, check_stats=True):
     loss = float(got["loss"].item())
     if dtype == "f32":
         assert np.abs(coef - ref["coef"]).max() <= 1e-4
-        assert abs(loss - ref["loss"]) <= 1e-4
+        # 1e-4 absolute is the bar of the tiny fp32 workload (token mean: the loss is O(1)).  A loss that is a SUM
+        # over hundreds of tokens (paper-literal normalisation) carries fp32 rounding of each term: scale with it.
+        tol = 1e-4 + (2e-6 * np.abs(ref["coef"] * ref["logp"]).sum() if f32_loss_scaled else 0.0)
+        assert abs(loss - ref["loss"]) <= tol, (loss, ref["loss"], tol)
     else:
         cs = np.abs(ref["coef"]).max()
         assert np.abs(coef - ref["coef"]).max() <= 2.5e-2 * cs + 1e-30      # coef ~ exp(logp): 2e-2 in logp
