@@ -57,28 +57,40 @@ def cpu_baseline(x, w, rows, rows_one_thread):
 
 
 def library_gemm(x, flops):
-    """Context, not part of the path: the vendor library's plain bf16 GEMM (torch.matmul -> hipBLASLt) of the same
-    contraction, logits = H_active W^T written to HBM, timed the same way on the same machine.  It shows what a
-    tuned GEMM reaches here under the chip's power limit; the path's kernels fuse their epilogues and never
-    write the logits."""
+    """Context, not part of the path: the vendor library's plain bf16 GEMMs (torch.matmul -> hipBLASLt) of the same
+    three contraction shapes, timed the same way on the same machine -- logits = H_active W^T written to HBM, and
+    the two gradient products with a stand-in dz of the right shape and layout (vocab-major, as the path stages it).
+    They show what a tuned GEMM reaches here under the chip's power limit; the path's kernels fuse their epilogues
+    and never write the logits."""
     import torch
     rows = x["mask"].reshape(-1).nonzero().squeeze(1)
     Hc = x["H"].index_select(0, rows).contiguous()
-    Wt = x["W"].t()
-    out = torch.empty(Hc.shape[0], Wt.shape[1], dtype=Hc.dtype, device=Hc.device)
-    for _ in range(3):
-        torch.matmul(Hc, Wt, out=out)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 10
-    e0.record()
-    for _ in range(reps):
-        torch.matmul(Hc, Wt, out=out)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
-    return {"what": "torch.matmul bf16 (hipBLASLt), [n_valid,d] x [d,V] -> logits in HBM, same shape", "ms": ms,
-            "achieved": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
-            "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    W = x["W"]
+    n, V, d = Hc.shape[0], W.shape[0], W.shape[1]
+    g = torch.Generator(device=Hc.device).manual_seed(3)
+    dzT = (torch.randn(V, n, generator=g, device=Hc.device, dtype=torch.float32) * 1e-5).to(Hc.dtype)   # [V, n]
+    logits = torch.empty(n, V, dtype=Hc.dtype, device=Hc.device)
+    dH = torch.empty(n, d, dtype=Hc.dtype, device=Hc.device)
+    dW = torch.empty(V, d, dtype=Hc.dtype, device=Hc.device)
+
+    def timed(f, reps=10):
+        for _ in range(3):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        return {"ms": ms, "achieved": flops / (ms * 1e-3) / 1e12, "frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+    res = timed(lambda: torch.matmul(Hc, W.t(), out=logits))
+    res.update({"what": "torch.matmul bf16 (hipBLASLt), [n_valid,d] x [d,V] -> logits in HBM, same shape",
+                "unit": "TFLOP/s",
+                "dH_shape": timed(lambda: torch.matmul(dzT.t(), W, out=dH)),      # dz [n,V] (stored vocab-major) x W [V,d]
+                "dW_shape": timed(lambda: torch.matmul(dzT, Hc, out=dW))})         # dz^T [V,n] x H [n,d]
+    return res
 
 
 def streaming_epilogue(L, x, w, t_loss_ms, dev, stream):
