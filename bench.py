@@ -125,6 +125,27 @@ def streaming_epilogue(L, x, w, t_loss_ms, dev, stream):
     return res
 
 
+def graph_replay(step, reps, median):
+    """The same step recorded once into a HIP graph and replayed: what a launch-bound (small) batch gains when the
+    caller captures the path, which it may, since the entry points only enqueue kernels."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(stream=side)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    graph.replay()
+    for a, b in ev:
+        a.record()
+        graph.replay()
+        b.record()
+    torch.cuda.synchronize()
+    return {"ms_per_step": median([a.elapsed_time(b) for a, b in ev]), "replays": reps,
+            "what": "one hipGraphLaunch per step (token_logprobs + loss_fwd + loss_bwd captured once)"}
+
+
 def measured_traffic(kernel):
     """Bytes per launch of `kernel` between L2 and the fabric (reads include Infinity-Cache hits), from the committed
     rocprofv3 FETCH_SIZE / WRITE_SIZE summary, already scaled by the plain-copy calibration.  None if absent."""
@@ -219,7 +240,7 @@ def main():
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
 
-    def step(e=None, ph=None):
+    def step(e=None, ph=None, stream=stream):
         if e:
             e[0].record(stream)
         logp, lse = L.token_logprobs(x["H"], x["W"], x["targets"], mask_flat, ws=ws_fwd, stream=stream)
@@ -331,6 +352,7 @@ def main():
     }
     if not args.no_extras:
         out["streaming_epilogue"] = streaming_epilogue(L, x, w, t_loss, dev, stream)
+        out["graph_replay"] = graph_replay(step, args.steps, median)
     if args.no_extras:
         del out["mfma_ceiling"], out["step_frac_of_measured_ceiling_8NVd"]
         del out["roofline"]["measured_ceiling"], out["roofline"]["frac_of_measured_ceiling"]
