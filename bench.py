@@ -318,6 +318,28 @@ def main():
     torch.cuda.synchronize()
     ceil_ms = median([a.elapsed_time(b) for a, b in cev])
     ceil_tflops = ceil_flops / (ceil_ms * 1e-3) / 1e12
+    # the same MFMA loop in the main loop's slot order, operands = values of this workload (rows of H and of W),
+    # with the main loop's LDS fragment reads and / or slab loads added back (no barrier, no wait)
+    ceil_traffic = None
+    if not args.no_extras:
+        panels = torch.empty(2, 256, 4096, dtype=torch.bfloat16, device=dev)
+        if w.dtype == "bf16" and d >= 4096 and N >= 256:
+            panels[0].copy_(x["H"][:256, :4096])
+            panels[1].copy_(x["W"][:256, :4096])
+        else:
+            panels[0].normal_()
+            panels[1].normal_(std=0.02)
+        ceil_traffic = {}
+        for name, mode in (("schedule_only", 0), ("lds_reads", 1), ("slab_loads", 2), ("lds_reads_and_slab_loads", 3)):
+            for _ in range(2):
+                fl = L.mfma_ceiling_traffic(mode, iters, panels, sink, stream=stream)
+            tev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+            for a, b in tev:
+                a.record(stream)
+                L.mfma_ceiling_traffic(mode, iters, panels, sink, stream=stream)
+                b.record(stream)
+            torch.cuda.synchronize()
+            ceil_traffic[name] = fl / (median([a.elapsed_time(b) for a, b in tev]) * 1e-3) / 1e12
     step_tflops = 4 * flops_gemm / (ms_step * 1e-3) / 1e12
 
     out = {
@@ -333,7 +355,12 @@ def main():
         "mfma_ceiling": {"what": "MFMA-only kernel (v_mfma_f32_16x16x32_bf16 from registers, 8 wavefronts x 8x4 "
                                  "blocks per CU, no LDS / memory traffic), %d x 2 k-steps per wavefront" % iters,
                          "ms": ceil_ms, "achieved": ceil_tflops, "unit": "TFLOP/s",
-                         "frac_of_published_peak": ceil_tflops / PEAK_BF16_TFLOPS},
+                         "frac_of_published_peak": ceil_tflops / PEAK_BF16_TFLOPS,
+                         "with_operand_traffic_TFLOPs": ceil_traffic,
+                         "with_operand_traffic_is": "the same MFMA loop in the main loop's slot order on this "
+                                                    "workload's operand values, plus the main loop's LDS fragment "
+                                                    "reads and / or L2->LDS slab loads; no barrier, no wait, "
+                                                    "operands resident in L2"},
         "step_frac_of_measured_ceiling_8NVd": step_tflops / ceil_tflops,
         "ms_token_logprobs": t_lp, "ms_loss_fwd": t_loss, "ms_loss_bwd": t_bwd,
         "ms_bwd_setup_kernels": t_setup,

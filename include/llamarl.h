@@ -258,6 +258,21 @@ llamarl_status llamarl_offpolicy_loss_bwd_phases(const void* H, const void* W, c
 llamarl_status llamarl_mfma_ceiling(int iters, float* sink, double* flops, void* stream);
 
 /*
+ * MEASUREMENT AID, outside the method: the loop of llamarl_mfma_ceiling in the slot order of the contraction
+ * kernels' main loop, with that loop's operand traffic added back piece by piece and still without any barrier or
+ * wait.  traffic bit 0: the twelve 16-byte fragment reads from LDS of every k-step; bit 1: the LDS-direct loads of
+ * one 64 KB operand slab per two k-steps (from `panels`, which stays in L2).  What the rate loses against traffic = 0
+ * is what that traffic costs: the chip is power-limited, so added traffic lowers the clock.
+ *
+ *   panels       device, 16-byte aligned, at least 4 MiB readable: two panels of 256 rows x 4096 bf16 whose values
+ *                are the operands of the MFMAs (the power the matrix pipes draw depends on them)
+ *   panel_bytes  bytes readable at panels (less than 4 MiB: LLAMARL_ERR_INVALID_ARG)
+ *   sink, flops  as for llamarl_mfma_ceiling
+ */
+llamarl_status llamarl_mfma_ceiling_traffic(int traffic, int iters, const void* panels, size_t panel_bytes,
+                                            float* sink, double* flops, void* stream);
+
+/*
  * Group-mean baseline (Sec. 6: from one prompt, n generations are sampled and the baseline is the mean of their
  * rewards, constant over the tokens of a generation):
  *     adv[p,i] = r[p,i] - (1/n) sum_j r[p,j]

@@ -21,7 +21,7 @@ PASS_LOGPROBS, PASS_LOSS_FWD, PASS_LOSS_BWD = 0, 1, 2
 
 EXPORTS = ("llamarl_workspace_bytes", "llamarl_last_error", "llamarl_version", "llamarl_token_logprobs",
            "llamarl_offpolicy_loss_fwd", "llamarl_offpolicy_loss_bwd", "llamarl_offpolicy_loss_bwd_phases",
-           "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling",
+           "llamarl_group_advantages", "llamarl_kl_shaped_rewards", "llamarl_mfma_ceiling", "llamarl_mfma_ceiling_traffic",
            "llamarl_offpolicy_loss_fwd_static", "llamarl_token_logprobs_partial", "llamarl_merge_partials",
            "llamarl_offpolicy_loss_bwd_slice", "llamarl_bwd_workspace_bytes", "llamarl_offpolicy_loss_bwd_chunked")
 
@@ -86,6 +86,8 @@ def load():
                                                        vp, sz, vp]
     lib.llamarl_mfma_ceiling.restype = ci
     lib.llamarl_mfma_ceiling.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.llamarl_mfma_ceiling_traffic.restype = ci
+    lib.llamarl_mfma_ceiling_traffic.argtypes = [ci, ci, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
     return lib
 
@@ -285,6 +287,16 @@ def mfma_ceiling(iters, sink, stream=None):
     flops = ctypes.c_double()
     _check(lib.llamarl_mfma_ceiling(int(iters), _ptr(sink), ctypes.byref(flops), _stream(stream)))
     return float(flops.value)
+
+
+def mfma_ceiling_traffic(traffic, iters, panels, sink, stream=None):
+    """llamarl_mfma_ceiling_traffic (measurement aid): the MFMA loop plus the main loop's LDS reads (traffic bit 0)
+    and slab loads (bit 1); returns the flop it executes.  panels: device tensor of at least 4 MiB."""
+    lib = load()
+    flops = ctypes.c_double(0.0)
+    _check(lib.llamarl_mfma_ceiling_traffic(int(traffic), int(iters), _ptr(panels), panels.numel() * panels.element_size(),
+                                            _ptr(sink), ctypes.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def token_logprobs_partial(H, W_slice, targets, v0, V_total, mask=None, ws=None, stream=None):

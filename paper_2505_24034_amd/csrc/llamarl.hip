@@ -346,6 +346,15 @@ llamarl_status run_bwd(const void* H, const void* W, const int32_t* targets, con
   return LLAMARL_OK;
 }
 
+typedef void (*ceiling_traffic_kernel_t)(int, float*, const void*);
+llamarl_status launch_ceiling_traffic(ceiling_traffic_kernel_t kernel, int grid, int iters, float* sink,
+                                      const void* panels, hipStream_t st) {
+  HIP_TRY(set_lds(kernel, MAINLOOP_LDS_BYTES));
+  kernel<<<dim3((unsigned)grid), dim3(NTHREADS), MAINLOOP_LDS_BYTES, st>>>(iters, sink, panels);
+  HIP_TRY(hipGetLastError());
+  return LLAMARL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -589,6 +598,24 @@ llamarl_status llamarl_mfma_ceiling(int iters, float* sink, double* flops, void*
   k_mfma_ceiling<<<dim3((unsigned)grid), dim3(NTHREADS), 0, reinterpret_cast<hipStream_t>(stream)>>>(iters, sink);
   HIP_TRY(hipGetLastError());
   // 16x16x32 MFMA = 2 * 16 * 16 * 32 flop; MB x NB of them per k-step and wavefront
+  *flops = (double)grid * (NTHREADS / 64) * (double)iters * CEILING_KSTEPS_PER_ITER * (MB * NB) * (2.0 * 16 * 16 * 32);
+  return LLAMARL_OK;
+}
+
+llamarl_status llamarl_mfma_ceiling_traffic(int traffic, int iters, const void* panels, size_t panel_bytes,
+                                            float* sink, double* flops, void* stream) {
+  if (!sink || !flops || !panels) return fail(LLAMARL_ERR_INVALID_ARG, "null pointer argument");
+  if (iters <= 0) return fail(LLAMARL_ERR_INVALID_ARG, "iters must be positive");
+  if (traffic < 0 || traffic > 3) return fail(LLAMARL_ERR_INVALID_ARG, "traffic must be 0 .. 3");
+  if (panel_bytes < CEILING_PANEL_BYTES || !aligned16(panels))
+    return fail(LLAMARL_ERR_INVALID_ARG, "panels must be 16-byte aligned and hold %zu bytes (got %zu)",
+                CEILING_PANEL_BYTES, panel_bytes);
+  const int grid = persistent_grid((int64_t)1 << 30);      // one workgroup per CU
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  static const ceiling_traffic_kernel_t kernels[4] = {k_mfma_ceiling_schedule, k_mfma_ceiling_lds_reads,
+                                                      k_mfma_ceiling_slab_loads, k_mfma_ceiling_reads_and_loads};
+  const llamarl_status s = launch_ceiling_traffic(kernels[traffic], grid, iters, sink, panels, st);
+  if (s != LLAMARL_OK) return s;
   *flops = (double)grid * (NTHREADS / 64) * (double)iters * CEILING_KSTEPS_PER_ITER * (MB * NB) * (2.0 * 16 * 16 * 32);
   return LLAMARL_OK;
 }

@@ -174,3 +174,10 @@ def test_new_entry_points_reject_bad_arguments(clib):
     assert st == binding.ERR_INVALID_ARG and b"aligned" in clib.llamarl_last_error()
     flops = ctypes.c_double()
     assert clib.llamarl_mfma_ceiling(0, fake(0), ctypes.byref(flops), None) == binding.ERR_INVALID_ARG
+    # the traffic variant: mode, iteration count and the size of the operand panels are checked on the host
+    assert clib.llamarl_mfma_ceiling_traffic(4, 10, fake(1), 1 << 22, fake(0), ctypes.byref(flops), None) == \
+        binding.ERR_INVALID_ARG
+    assert clib.llamarl_mfma_ceiling_traffic(3, 0, fake(1), 1 << 22, fake(0), ctypes.byref(flops), None) == \
+        binding.ERR_INVALID_ARG
+    assert clib.llamarl_mfma_ceiling_traffic(3, 10, fake(1), (1 << 22) - 1, fake(0), ctypes.byref(flops), None) == \
+        binding.ERR_INVALID_ARG and b"panels" in clib.llamarl_last_error()
