@@ -370,3 +370,19 @@ def test_phase_event_variant_of_the_backward_gives_the_same_bits(lib):
         assert ms.value >= 0.0
     for e in evs:
         hip.hipEventDestroy(ctypes.c_void_p(e))
+
+
+def test_ceiling_kernels_run_and_report_their_flop(lib):
+    # measurement aids: every variant runs to completion on a small iteration count, leaves `sink` alone and
+    # reports 256 (or fewer) workgroups x 8 wavefronts x iters x 2 k-steps x 32 MFMAs x 16384 flop
+    sink = torch.zeros(1, device="cuda")
+    panels = torch.randn(2, 256, 4096, device="cuda").to(torch.bfloat16)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    want = min(cus, 256) * 8 * 50 * 2 * 32 * 16384.0
+    assert lib.mfma_ceiling(50, sink) == want
+    for mode in range(4):
+        assert lib.mfma_ceiling_traffic(mode, 50, panels, sink) == want
+    torch.cuda.synchronize()
+    assert float(sink) == 0.0
+    with pytest.raises(lib.LlamarlError):
+        lib.mfma_ceiling_traffic(1, 50, panels[:1], sink)          # one panel only: too small
