@@ -22,6 +22,17 @@ def run_hip(lib, x, rho=2.0, norm_mode=0, grad_loss=1.0, clip_mode=0, eps=(0.2, 
 
 
 def run_oracle(x, rho=2.0, norm_mode=0, grad_loss=1.0, clip_mode=0, eps=(0.2, 0.2)):
+    ref = _oracle_step(x, rho, norm_mode, grad_loss, clip_mode, eps)
+    # natural magnitude of a gradient entry, from the inputs alone: |dz| <= |g coef|, and an entry of dH (dW) is a
+    # sum of V (N_valid) such terms times an entry of W (H) with mixed signs.  Only used as the absolute floor of
+    # comparisons whose reference is exactly zero (see check_grad).
+    c = abs(grad_loss) * float(np.abs(ref["coef"]).max())
+    ref["floor_dH"] = 1e-5 * c * float(x["W"].abs().max()) * np.sqrt(x["W"].shape[0])
+    ref["floor_dW"] = 1e-5 * c * float(x["H"].abs().max()) * np.sqrt(max(1.0, float(ref["stats"][0])))
+    return ref
+
+
+def _oracle_step(x, rho, norm_mode, grad_loss, clip_mode, eps):
     return orc.aipo_step(synth.to_oracle(x["H"]), synth.to_oracle(x["W"]), synth.to_oracle(x["targets"]),
                          synth.to_oracle(x["mu_logp"]), synth.to_oracle(x["adv"]), synth.to_oracle(x["mask"]),
                          rho, norm_mode, grad_loss, clip_mode, eps[0], eps[1])
@@ -31,9 +42,11 @@ def f64(t):
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-def check_grad(name, got, ref, dtype):
+def check_grad(name, got, ref, dtype, floor=0.0):
     """fp32 workload: |delta| <= 1e-4 everywhere.  bf16 workloads: relative Frobenius error <= 1e-2 and
-    max |delta| <= 1e-2 * max |ref|."""
+    max |delta| <= 1e-2 * max |ref|.  floor: absolute slack per entry for references that are exactly zero in fp64
+    (a one-entry vocabulary: softmax = 1, dz = 0) where fp32 leaves rounding-sized values and "relative" has no
+    meaning; 1e-5 of the natural magnitude of an entry, far below 1e-2 of any non-degenerate reference."""
     got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, name
     assert np.all(np.isfinite(got)), name + " has non-finite entries"
@@ -42,9 +55,20 @@ def check_grad(name, got, ref, dtype):
         assert err <= 1e-4, "%s: max |delta| = %.3g" % (name, err)
         return
     scale = np.abs(ref).max()
-    fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300)
-    assert fro <= 1e-2, "%s: relative Frobenius error %.3g" % (name, fro)
-    assert err <= 1e-2 * scale + 1e-30, "%s: max |delta| = %.3g vs max |ref| = %.3g" % (name, err, scale)
+    dn, rn = np.linalg.norm(got - ref), np.linalg.norm(ref)
+    assert dn <= 1e-2 * rn + floor * np.sqrt(got.size), "%s: relative Frobenius error %.3g" % (name, dn / max(rn, 1e-300))
+    assert err <= 1e-2 * scale + floor + 1e-30, "%s: max |delta| = %.3g vs max |ref| = %.3g" % (name, err, scale)
+
+
+def same_up_to_summation_order(a, b):
+    """Two results of the same contraction whose K range was cut into different parts (the plan that splits the
+    last tiles of a store contraction depends on how many tiles there are): fp32 sums that differ by rounding, and
+    for 16-bit outputs two roundings of such sums, at most one unit in the last place apart."""
+    a32, b32 = a.to(torch.float32), b.to(torch.float32)
+    scale = float(b32.abs().max())
+    if a.dtype == torch.float32:
+        return bool(((a32 - b32).abs() <= 4e-6 * scale).all())
+    return bool(((a32 - b32).abs() <= 2.0 ** -7 * b32.abs() + 4e-6 * scale).all())
 
 
 def check_all(got, ref, dtype, check_stats=True, f32_loss_scaled=False):
@@ -65,14 +89,20 @@ def check_all(got, ref, dtype, check_stats=True, f32_loss_scaled=False):
     else:
         cs = np.abs(ref["coef"]).max()
         assert np.abs(coef - ref["coef"]).max() <= 2.5e-2 * cs + 1e-30      # coef ~ exp(logp): 2e-2 in logp
+        # relative to the loss's own terms, plus fp32 rounding of log-probs that are exactly 0 in fp64 (V = 1)
         scale = np.abs(ref["coef"] * ref["logp"]).sum()
-        assert abs(loss - ref["loss"]) <= 1e-2 * scale + 1e-30, (loss, ref["loss"], scale)
+        assert abs(loss - ref["loss"]) <= 1e-2 * scale + 1e-5 * np.abs(ref["coef"]).sum() + 1e-30, \
+            (loss, ref["loss"], scale)
     if check_stats:
         st = f64(got["stats"])
         assert st[0] == ref["stats"][0] and st[4] == ref["stats"][4]
-        assert np.allclose(st[1:4], ref["stats"][1:4], rtol=0, atol=(1e-4 if dtype == "f32" else 2.5e-2))
-    check_grad("dH", f64(got["dH"]), ref["dH"], dtype)
-    check_grad("dW", f64(got["dW"]), ref["dW"], dtype)
+        tol = 1e-4 if dtype == "f32" else 2.5e-2
+        assert abs(st[1] - ref["stats"][1]) <= tol and abs(st[3] - ref["stats"][3]) <= tol
+        # clip fraction: a ratio within fp32 rounding of the bound may be counted on either side; among thousands of
+        # tokens one or two such ratios do occur
+        assert abs(st[2] - ref["stats"][2]) <= tol + 2.0 / max(1.0, ref["stats"][0])
+    check_grad("dH", f64(got["dH"]), ref["dH"], dtype, ref.get("floor_dH", 0.0))
+    check_grad("dW", f64(got["dW"]), ref["dW"], dtype, ref.get("floor_dW", 0.0))
 
 
 def sample_rows(x, n, rng):

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import synth
-from parity_util import check_all, check_grad, f64, run_hip, run_oracle
+from parity_util import check_all, check_grad, f64, run_hip, run_oracle, same_up_to_summation_order
 
 pytestmark = pytest.mark.gpu
 W8 = synth.WORKLOADS["llama3_8b"]
@@ -202,7 +202,8 @@ def test_backward_in_row_passes_with_a_bounded_workspace(lib, w):
         torch.cuda.synchronize()
         check_grad("dH (row passes)", f64(dH), ref["dH"], w.dtype)
         check_grad("dW (row passes)", f64(dW), ref["dW"], w.dtype)
-        assert torch.equal(dH, one["dH"])                  # a dH row belongs to one pass: same contraction, same bits
+        # a dH row belongs to one pass: the same contraction, K possibly split at other places
+        assert same_up_to_summation_order(dH, one["dH"])
         if dW_dtype == torch.float32:
             assert torch.allclose(dW, one["dW"], rtol=0, atol=2e-6 * float(one["dW"].abs().max()))
     # accumulate_dW holds for the first pass too
