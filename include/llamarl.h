@@ -27,7 +27,7 @@
  *    (16-byte rows).  N, V are arbitrary (>= 1).  W may exceed 4 GiB; H must be
  *    smaller than 2 GiB (its rows are gathered with 32-bit offsets) and a
  *    256-row panel of any operand smaller than 2 GiB: LLAMARL_ERR_UNSUPPORTED
- *    otherwise.
+ *    otherwise (a larger batch is taken in several calls, dW accumulating).
  *  - Results are deterministic: the same inputs give the same bits, run to run
  *    (no floating-point atomics anywhere).
  */
@@ -188,6 +188,9 @@ llamarl_status llamarl_offpolicy_loss_bwd(const void* H, const void* W, const in
  * nothing to do and cost microseconds.  A caller who knows that at most R rows are active bounds the workspace at
  * no cost; a smaller R trades it for one read-modify-write of dW per extra pass -- and, for a bf16 dW, one more
  * rounding to bf16 per pass (use dW_dt = LLAMARL_F32 when that matters).  max_rows_per_pass = 0 means N.
+ * A dH row comes out of one pass only; it equals the one-pass result up to the order of its fp32 sums (where the
+ * contraction's K range is cut depends on how many tiles the pass has), and is reproducible run to run like
+ * everything else.
  *   ws >= llamarl_bwd_workspace_bytes(N, d, V, dt, max_rows_per_pass)   (returns 0 for invalid sizes)
  */
 size_t llamarl_bwd_workspace_bytes(int64_t N, int64_t d, int64_t V, llamarl_dtype dt, int64_t max_rows_per_pass);
