@@ -135,13 +135,18 @@ struct TileGemmTN {
   // bits 3..4, so bit 3 of the swizzle is folded into the base and fx carries bits 1..2 only.
   __device__ __forceinline__ static const char* blk(const char* base, int b, int fx) { return base + ((b * 32) ^ fx); }
 
-  // One k-step (32 k-rows); same slot table as k_step in gemm_nt.h.  pa / pb: slab base + this lane's row and
-  // byte offset for the k-step; fx: the lane's chunk swizzle in bytes.
+  // One k-step (32 k-rows); the slot table of k_step in gemm_nt.h with the barrier of a slab's last k-step moved up
+  // to slot 4 and the slab loads to the odd slots 5 .. 19.  Every fragment is two LDS instructions here, so the 24
+  // reads of the next slab need the room: barrier at slot 8 / loads from slot 11 measured 3.4 % slower for the dH
+  // contraction, barrier at slot 6: 0.8 % slower, at slot 2: 0.5 % slower; loads on even slots (where the fragment
+  // reads sit): 4 - 6 % slower.  (The K-contiguous loop does not care: +-0.5 % for the same moves.)
+  // pa / pb: slab base + this lane's row and byte offset for the k-step; fx: the lane's chunk swizzle in bytes.
   template <bool BAR, bool NEXT, bool FETCH>
   __device__ __forceinline__ static void k_step(frag_t (&a)[MB], const frag_t (&bc)[NB], frag_t (&bn)[NB],
                                                 f32x4_t (&acc)[MB][NB], const char* pa_cur, const char* pa_nxt,
                                                 const char* pb_nxt, int fx, int fxb, const Fetch* f) {
-    constexpr int TB = 8;
+    constexpr int TB = 4;      // barrier slot: a[7], the last read of the slab, was issued at slot 0
+    constexpr int LS = 5;      // first of the eight load slots (every other slot from here)
     static_assert(MB == 8 && NB == 4, "slot table written for an 8 x 4 wave tile");
 #pragma unroll
     for (int t = 0; t < MB * NB; ++t) {
@@ -158,8 +163,8 @@ struct TileGemmTN {
         LLAMARL_FENCE();
       }
       if (NEXT) {
-        if (t == TB) a[0] = read_frag(blk(pa_nxt, 0, fx));
-        if (t == TB + 1) a[1] = read_frag(blk(pa_nxt, 1, fx));
+        if (t == 4) a[0] = read_frag(blk(pa_nxt, 0, fx));        // block 0 is done after slot 3, block 1 after slot 7
+        if (t == 8) a[1] = read_frag(blk(pa_nxt, 1, fx));
         if (t >= 12 && (t & 3) == 0) a[ib - 1] = read_frag(blk(pa_nxt, ib - 1, fx));
         if (t == 10) bn[0] = read_frag(blk(pb_nxt, 0, fxb));
         if (t == 14) bn[1] = read_frag(blk(pb_nxt, 1, fxb));
@@ -167,8 +172,8 @@ struct TileGemmTN {
         if (t == 22) bn[3] = read_frag(blk(pb_nxt, 3, fxb));
         LLAMARL_FENCE();
       }
-      if (FETCH && t >= 11 && t <= 25 && (t & 1) == 1) {
-        const int n = (t - 11) >> 1;
+      if (FETCH && t >= LS && t <= LS + 14 && ((t - LS) & 1) == 0) {
+        const int n = (t - LS) >> 1;
         if (n < 4) f->la->issue_one(f->sa, n, f->wave);
         else f->lb->issue_one(f->sb, n - 4, f->wave);
         LLAMARL_FENCE();
