@@ -268,10 +268,16 @@ __device__ __forceinline__ constexpr int snake_col(int t) { return ((t >> 2) & 1
 //   BAR    : this is the last k-step of a slab that has a successor.  By slot 0 every read of the slab has been
 //            issued, so the barrier can sit as early as slot TB = 8: it waits for this thread's share of the next
 //            slab (vmcnt) and for its own reads (lgkmcnt), then the 24 MFMAs left run from registers while the
-//            next slab's fragments are read and, with FETCH, the slab after that is requested (one load per slot,
-//            into the stage this barrier just freed).
+//            next slab's fragments are read and, with FETCH, the slab after that is requested (one load every
+//            other slot from slot LS on, into the stage this barrier just freed).  LS = 11 for the logits kernels;
+//            the store contraction (dW) asks two slots earlier, which measured 1 - 1.5 % faster for it at three of
+//            four shapes and the same at the fourth, while the logits kernels lose 0.5 % with it at the longest
+//            batch.  Slots of the same parity as the fragment reads (even) are 4 - 6 % slower.
 //   NEXT   : there is a next k-step (pa_nxt / pb_nxt: lane's fragment address of its blocks 0).
-template <typename TT, bool BAR, bool NEXT, bool FETCH>
+//   LS     : a template parameter although only its value matters: every specialisation of this template must be
+//            called from ONE function instantiation only -- the host pass of hipcc (ROCm 7.2) rejects a second
+//            caller of the same specialisation ("substitution failure", no reason given; the device pass accepts it).
+template <typename TT, bool BAR, bool NEXT, bool FETCH, int LS>
 __device__ __forceinline__ void k_step(typename TT::frag_t (&a)[MB], const typename TT::frag_t (&bc)[NB],
                                        typename TT::frag_t (&bn)[NB], f32x4_t (&acc)[MB][NB], const char* pa_cur,
                                        const char* pa_nxt, const char* pb_nxt, const SlabFetch<TT>* sf) {
@@ -302,8 +308,8 @@ __device__ __forceinline__ void k_step(typename TT::frag_t (&a)[MB], const typen
       if (t == 22) bn[3] = *reinterpret_cast<const frag_t*>(pb_nxt + 3 * BLOCK_BYTES);
       LLAMARL_FENCE();
     }
-    if (FETCH && t >= 11 && t <= 25 && (t & 1) == 1) {
-      const int n = (t - 11) >> 1;
+    if (FETCH && t >= LS && t <= LS + 14 && ((t - LS) & 1) == 0) {
+      const int n = (t - LS) >> 1;
       if (n < 4) sf->la->issue_one(sf->dst, n, sf->k0, sf->K, sf->wave, sf->lane, true);
       else sf->lb->issue_one(sf->dst + SLAB_A_BYTES, n - 4, sf->k0, sf->K, sf->wave, sf->lane, true);
       LLAMARL_FENCE();
@@ -321,7 +327,7 @@ __device__ __forceinline__ void k_step(typename TT::frag_t (&a)[MB], const typen
 // GATHER_B: the B panel is gathered -- B_tile is then the base of the whole matrix with b_total rows and
 // tile row r is its row b_rows[r].  QUAD_B: output columns are quad-interleaved over the lane's four column blocks
 // (tile_row_of); the epilogue must then take its columns from LanePos::col_quad().
-template <typename TT>
+template <typename TT, int LOAD_SLOT = 11>
 struct TileGemm {
   typedef typename TT::frag_t frag_t;
   static constexpr int BK = 8 * TT::EPC;
@@ -401,22 +407,27 @@ struct TileGemm {
       char* cur = smem + (kt & 1) * STAGE_BYTES;
       const char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      k_step<TT, false, true, false>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1], nullptr);
+      k_step<TT, false, true, false, LOAD_SLOT>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1],
+                                                nullptr);
       const SlabFetch<TT> sf{&la, &lb, cur, (kt + 2) * BK, K, wave, lane};
-      k_step<TT, true, true, true>(a, b1, b0, acc, cur + a_addr[1], nxt + a_addr[0], nxt + b_addr[0], &sf);
+      k_step<TT, true, true, true, LOAD_SLOT>(a, b1, b0, acc, cur + a_addr[1], nxt + a_addr[0], nxt + b_addr[0],
+                                              &sf);
     }
     if (nk >= 2) {
       const char* cur = smem + ((nk - 2) & 1) * STAGE_BYTES;
       const char* nxt = smem + ((nk - 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      k_step<TT, false, true, false>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1], nullptr);
-      k_step<TT, true, true, false>(a, b1, b0, acc, cur + a_addr[1], nxt + a_addr[0], nxt + b_addr[0], nullptr);
+      k_step<TT, false, true, false, LOAD_SLOT>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1],
+                                                nullptr);
+      k_step<TT, true, true, false, LOAD_SLOT>(a, b1, b0, acc, cur + a_addr[1], nxt + a_addr[0], nxt + b_addr[0],
+                                               nullptr);
     }
     {
       const char* cur = smem + ((nk - 1) & 1) * STAGE_BYTES;
       LLAMARL_FENCE();
-      k_step<TT, false, true, false>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1], nullptr);
-      k_step<TT, false, false, false>(a, b1, b0, acc, cur + a_addr[1], nullptr, nullptr, nullptr);
+      k_step<TT, false, true, false, LOAD_SLOT>(a, b0, b1, acc, cur + a_addr[0], cur + a_addr[1], cur + b_addr[1],
+                                                nullptr);
+      k_step<TT, false, false, false, LOAD_SLOT>(a, b1, b0, acc, cur + a_addr[1], nullptr, nullptr, nullptr);
     }
   }
 };

@@ -34,6 +34,7 @@ __host__ __device__ __forceinline__ int64_t packed_pitch(int64_t n_rows) {
 }
 // Patch rows (TileSchedule::init).  Measured at the Llama-3-8B shape with patches dealt round-robin over the XCDs:
 // logits kernels 4 and 8 tie (2: +1 %); dW 8 (4: +1.6 %, 2: +5 %); dH: see PATCH_ROWS_KMAJOR.
+constexpr int STORE_LOAD_SLOT = 9;      // first slab-load slot of the K-contiguous store contraction (see k_step)
 constexpr int PATCH_ROWS_LOGITS = 4;
 constexpr int PATCH_ROWS_STORE = 8;
 // dH on k-major operands, whole tiles of K = V, when the output is at most 16 tiles wide (d <= 4096): 16 x 2
@@ -650,8 +651,8 @@ __device__ __forceinline__ StoreTile<TT> store_tile_of(const StorePlan& plan, co
   return t;
 }
 template <typename TT>
-__device__ __forceinline__ void store_fetch(TileGemm<TT>& g, const StorePlan& plan, const StoreArgs& a, int item,
-                                            int64_t M, int64_t K, char* smem) {
+__device__ __forceinline__ void store_fetch(TileGemm<TT, STORE_LOAD_SLOT>& g, const StorePlan& plan, const StoreArgs& a,
+                                            int item, int64_t M, int64_t K, char* smem) {
   typedef typename TT::store_t st;
   const StoreTile<TT> t = store_tile_of<TT>(plan, a, item, M, K);
   if (t.k_len > 0)
@@ -733,7 +734,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_store(StoreArgs a) {
     a.plan_out[0] = plan.whole; a.plan_out[1] = plan.rem; a.plan_out[2] = plan.splits; a.plan_out[3] = tiles_m;
   }
   if (!plan.has_item()) return;                      // block-uniform
-  typename std::conditional<KMAJOR, TileGemmTN, TileGemm<TT>>::type g;
+  typename std::conditional<KMAJOR, TileGemmTN, TileGemm<TT, STORE_LOAD_SLOT>>::type g;
   int id = plan.take();
   store_fetch(g, plan, a, id, M, K, smem);
   while (true) {
